@@ -1,0 +1,134 @@
+/*
+ * aeris_winattn.h -- C ABI of the MI355X (gfx950) shifted-window attention library.
+ *
+ * The operation is the attention step of the AERIS Swin diffusion transformer
+ * (paper, "AERIS Model Architecture": the embedded image is partitioned into
+ * square windows that are shifted on alternating layers, queries/keys/values
+ * are projected per head, and dot-product attention runs inside each window;
+ * "SWiPe", Overview: windows are disjoint, no halo).  Pixel-level tokens live
+ * on a [B, H_lat, W_lon, heads, head_dim] grid.
+ *
+ * For window (wy, wx) and local token (r, c) the grid point is
+ *     y = (wy*win_h + r + shift_h) mod H_lat,  x = (wx*win_w + c + shift_w) mod W_lon
+ * (cyclic in both axes; Fig. 2a, right panel).  Within a window and head
+ *     S = softmax_scale * Q K^T,  masked where region(i) != region(j),
+ *     LSE_i = ln sum_j exp(S_ij),  P = exp(S - LSE),  O = P V,
+ * and for the backward pass, given dO,
+ *     dV = P^T dO,  dP = dO V^T,  delta_i = sum_c dO_ic O_ic,
+ *     dS = P o (dP - delta),  dQ = scale * dS K,  dK = scale * dS^T Q.
+ * Results are written at the original (unshifted) grid coordinates.
+ *
+ * The paper does not mention a boundary mask for shifted windows.  Three
+ * policies are offered; regions are defined in the shifted frame, per axis of
+ * length L, window side ws, shift s: coordinate u is in region 0 if u < L-ws,
+ * 1 if L-ws <= u < L-s, 2 otherwise.
+ *     AERIS_MASK_NONE  no mask (periodic wrap on both axes)
+ *     AERIS_MASK_LAT   latitude regions separate (the pole-to-pole seam), the
+ *                      longitude seam stays periodic
+ *     AERIS_MASK_SWIN  latitude and longitude regions both separate, as in the
+ *                      masked shifted-window attention of the Swin paper
+ *
+ * Arithmetic: bf16 operands, fp32 accumulation (paper, "Mixed precision"),
+ * P rounded to bf16 before the P V product, outputs rounded to nearest even.
+ *
+ * All pointers are DEVICE pointers on the current HIP device unless stated.
+ * The caller owns every buffer.  The library allocates nothing, frees nothing
+ * and never synchronises: every call only enqueues kernels on `hip_stream`
+ * (a hipStream_t passed as void*; NULL is the default stream).  Inputs are
+ * read-only, outputs are fully overwritten.  Calls are thread-safe; there is
+ * no global state.  Arguments are validated before anything is launched, so
+ * every error except AERIS_ERR_HIP_LAUNCH is reachable without a GPU.
+ */
+#ifndef AERIS_WINATTN_H
+#define AERIS_WINATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { AERIS_MASK_NONE = 0, AERIS_MASK_LAT = 1, AERIS_MASK_SWIN = 2 };
+enum { AERIS_DT_BF16 = 0, AERIS_DT_F32 = 1 };
+
+enum {
+  AERIS_OK = 0,
+  AERIS_ERR_NULL_POINTER = -1,
+  AERIS_ERR_INVALID_SHAPE = -2,        /* a dimension <= 0, or a stride too small   */
+  AERIS_ERR_NOT_DIVISIBLE = -3,        /* window does not divide the grid           */
+  AERIS_ERR_BAD_SHIFT = -4,            /* need 0 <= shift < window                  */
+  AERIS_ERR_BAD_MASK = -5,
+  AERIS_ERR_UNSUPPORTED_HEAD_DIM = -6, /* head_dim must be 32, 64 or 128            */
+  AERIS_ERR_MISALIGNED = -7,           /* 16-byte alignment of pointers and strides */
+  AERIS_ERR_WORKSPACE_TOO_SMALL = -8,
+  AERIS_ERR_WINDOW_TOO_LARGE = -9,     /* win_h*win_w > AERIS_MAX_WINDOW_TOKENS     */
+  AERIS_ERR_BAD_DTYPE = -10,
+  AERIS_ERR_HIP_LAUNCH = -11           /* hipGetLastError() after a launch          */
+};
+
+/* Largest window (tokens) the kernels' on-chip offset table holds. */
+#define AERIS_MAX_WINDOW_TOKENS 8192
+
+typedef struct {
+  int32_t B, H_lat, W_lon, heads, head_dim; /* grid; head_dim in {32, 64, 128}               */
+  int32_t win_h, win_w;                     /* window; must divide H_lat, W_lon              */
+  int32_t shift_h, shift_w;                 /* cyclic shift, 0 <= shift < win                */
+  int32_t mask_policy;                      /* AERIS_MASK_*                                  */
+  float softmax_scale;                      /* <= 0 selects 1/sqrt(head_dim)                 */
+  int32_t out_dtype;                        /* AERIS_DT_*: type of O, dQ, dK, dV             */
+  /* Element strides between tokens and between heads.  0 selects the compact
+   * layout (tok = heads*head_dim, head = head_dim).  qkv_* apply to q, k, v and
+   * to dq, dk, dv (a packed QKV buffer is passed without a copy); o_* apply to
+   * o and d_o.  Batch and row strides follow: row = W_lon*tok, batch = H_lat*row.
+   * Strides must be multiples of 8 elements. */
+  int64_t qkv_tok_stride, qkv_head_stride;
+  int64_t o_tok_stride, o_head_stride;
+} aeris_winattn_params;
+
+/*
+ * Forward (Model Architecture section: window partition + shift, dot-product
+ * attention per window and head).
+ *   q, k, v : bf16 [B, H_lat, W_lon, heads, head_dim] with the qkv strides, read-only
+ *   o       : out_dtype, same logical shape with the o strides, overwritten
+ *   lse     : float32 [B, heads, H_lat, W_lon] compact, natural-log LSE of the
+ *             scaled, masked logits, at original grid coordinates, overwritten
+ * Returns AERIS_OK or a negative AERIS_ERR_* code; on error nothing was launched
+ * (except AERIS_ERR_HIP_LAUNCH, which reports a failed launch).
+ */
+int aeris_winattn_fwd(const aeris_winattn_params* p, const void* q, const void* k,
+                      const void* v, void* o, float* lse, void* hip_stream);
+
+/* Bytes of device workspace the backward pass needs (the delta vector,
+ * float32 [B, heads, H_lat, W_lon]).  Returns 0 if the parameters are invalid. */
+size_t aeris_winattn_bwd_workspace_bytes(const aeris_winattn_params* p);
+
+/*
+ * Backward ("forward and backward pass with BF16 activations", Software
+ * Environment section; formulas above).  Recomputes P from the saved LSE.
+ *   q, k, v     : as in the forward call, read-only
+ *   o, lse      : the forward outputs (o must have been written as bf16), read-only
+ *   d_o         : bf16, layout of o, read-only
+ *   dq, dk, dv  : out_dtype, layout of q/k/v, overwritten
+ *   workspace   : >= aeris_winattn_bwd_workspace_bytes(p) bytes, 16-byte aligned,
+ *                 contents undefined before and after
+ * Deterministic: no atomics are used, results are bitwise reproducible.
+ */
+int aeris_winattn_bwd(const aeris_winattn_params* p, const void* q, const void* k,
+                      const void* v, const void* o, const float* lse, const void* d_o,
+                      void* dq, void* dk, void* dv, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
+
+/* Checks a parameter block without launching (host only): AERIS_OK or an error. */
+int aeris_winattn_validate(const aeris_winattn_params* p);
+
+/* Static, never-freed description of an error code. */
+const char* aeris_winattn_strerror(int code);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int aeris_winattn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AERIS_WINATTN_H */

@@ -1,0 +1,147 @@
+"""ctypes binding of libaeris_winattn.so: same names as the C entry points.
+
+Argument marshalling only.  PyTorch supplies device memory and the current HIP
+stream; every step of the computation runs in the library's kernels.  There is
+no fallback: if the library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libaeris_winattn.so")
+
+AERIS_MASK_NONE, AERIS_MASK_LAT, AERIS_MASK_SWIN = 0, 1, 2
+AERIS_DT_BF16, AERIS_DT_F32 = 0, 1
+
+EXPORTS = ("aeris_winattn_fwd", "aeris_winattn_bwd", "aeris_winattn_bwd_workspace_bytes",
+           "aeris_winattn_validate", "aeris_winattn_strerror", "aeris_winattn_version")
+
+
+class aeris_winattn_params(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H_lat", ctypes.c_int32), ("W_lon", ctypes.c_int32),
+                ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("win_h", ctypes.c_int32), ("win_w", ctypes.c_int32),
+                ("shift_h", ctypes.c_int32), ("shift_w", ctypes.c_int32),
+                ("mask_policy", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("out_dtype", ctypes.c_int32),
+                ("qkv_tok_stride", ctypes.c_int64), ("qkv_head_stride", ctypes.c_int64),
+                ("o_tok_stride", ctypes.c_int64), ("o_head_stride", ctypes.c_int64)]
+
+
+class AerisError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s failed: %d (%s)" % (where, code, aeris_winattn_strerror(code)))
+
+
+_lib = None
+
+
+def load():
+    """Load the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libaeris_winattn.so is not built: run "
+                          "`python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(expected at %s)" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    P = ctypes.POINTER(aeris_winattn_params)
+    vp = ctypes.c_void_p
+    lib.aeris_winattn_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp]
+    lib.aeris_winattn_fwd.restype = ctypes.c_int
+    lib.aeris_winattn_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                      ctypes.c_size_t, vp]
+    lib.aeris_winattn_bwd.restype = ctypes.c_int
+    lib.aeris_winattn_bwd_workspace_bytes.argtypes = [P]
+    lib.aeris_winattn_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.aeris_winattn_validate.argtypes = [P]
+    lib.aeris_winattn_validate.restype = ctypes.c_int
+    lib.aeris_winattn_strerror.argtypes = [ctypes.c_int]
+    lib.aeris_winattn_strerror.restype = ctypes.c_char_p
+    lib.aeris_winattn_version.argtypes = []
+    lib.aeris_winattn_version.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def make_params(shape, win, shift, mask=AERIS_MASK_NONE, scale=0.0, out_dtype=AERIS_DT_BF16,
+                qkv_strides=(0, 0), o_strides=(0, 0)):
+    B, H, W, nh, d = shape
+    return aeris_winattn_params(B, H, W, nh, d, win[0], win[1], shift[0], shift[1], mask,
+                                float(scale or 0.0), out_dtype,
+                                qkv_strides[0], qkv_strides[1], o_strides[0], o_strides[1])
+
+
+def aeris_winattn_version():
+    return load().aeris_winattn_version()
+
+
+def aeris_winattn_strerror(code):
+    return load().aeris_winattn_strerror(int(code)).decode()
+
+
+def aeris_winattn_validate(params):
+    return load().aeris_winattn_validate(ctypes.byref(params))
+
+
+def aeris_winattn_bwd_workspace_bytes(params):
+    return load().aeris_winattn_bwd_workspace_bytes(ctypes.byref(params))
+
+
+def _stream():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _torch_out_dtype(out_dtype):
+    import torch
+    return torch.float32 if out_dtype == AERIS_DT_F32 else torch.bfloat16
+
+
+def aeris_winattn_fwd(q, k, v, win, shift, mask=AERIS_MASK_NONE, scale=None,
+                      out_dtype=AERIS_DT_BF16, o=None, lse=None):
+    """q, k, v: contiguous torch.bfloat16 device tensors [B,H,W,heads,d].
+    Returns (o, lse); buffers are allocated with torch unless passed in."""
+    import torch
+    B, H, W, nh, d = q.shape
+    for t in (q, k, v):
+        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.shape == q.shape
+    p = make_params(q.shape, win, shift, mask, scale, out_dtype)
+    if o is None:
+        o = torch.empty(q.shape, dtype=_torch_out_dtype(out_dtype), device=q.device)
+    if lse is None:
+        lse = torch.empty((B, nh, H, W), dtype=torch.float32, device=q.device)
+    rc = load().aeris_winattn_fwd(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                  o.data_ptr(), lse.data_ptr(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_winattn_fwd")
+    return o, lse
+
+
+def aeris_winattn_bwd(q, k, v, o, lse, d_o, win, shift, mask=AERIS_MASK_NONE, scale=None,
+                      out_dtype=AERIS_DT_BF16, dq=None, dk=None, dv=None, workspace=None):
+    """Returns (dq, dk, dv).  o must be the forward output in ``out_dtype``."""
+    import torch
+    p = make_params(q.shape, win, shift, mask, scale, out_dtype)
+    odt = _torch_out_dtype(out_dtype)
+    assert o.dtype == odt and d_o.dtype == torch.bfloat16 and lse.dtype == torch.float32
+    for t in (q, k, v, o, d_o, lse):
+        assert t.is_cuda and t.is_contiguous()
+    if dq is None:
+        dq = torch.empty(q.shape, dtype=odt, device=q.device)
+    if dk is None:
+        dk = torch.empty(q.shape, dtype=odt, device=q.device)
+    if dv is None:
+        dv = torch.empty(q.shape, dtype=odt, device=q.device)
+    need = aeris_winattn_bwd_workspace_bytes(p)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    rc = load().aeris_winattn_bwd(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                  o.data_ptr(), lse.data_ptr(), d_o.data_ptr(), dq.data_ptr(),
+                                  dk.data_ptr(), dv.data_ptr(), workspace.data_ptr(),
+                                  workspace.numel() * workspace.element_size(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_winattn_bwd")
+    return dq, dk, dv

@@ -1,0 +1,145 @@
+// C ABI of the shifted-window attention library: argument validation,
+// parameter derivation and dispatch.  See include/aeris_winattn.h for the
+// contract of every entry point.
+#include "aeris_winattn.h"
+
+#include <math.h>
+
+#include "winattn_launch.hpp"
+
+namespace {
+
+struct Strides {
+  long long qkv_tok, qkv_head, o_tok, o_head;
+};
+
+int resolve(const aeris_winattn_params* p, Strides* s) {
+  if (!p) return AERIS_ERR_NULL_POINTER;
+  if (p->B <= 0 || p->H_lat <= 0 || p->W_lon <= 0 || p->heads <= 0 || p->win_h <= 0 ||
+      p->win_w <= 0)
+    return AERIS_ERR_INVALID_SHAPE;
+  if (p->head_dim != 32 && p->head_dim != 64 && p->head_dim != 128)
+    return AERIS_ERR_UNSUPPORTED_HEAD_DIM;
+  if (p->H_lat % p->win_h != 0 || p->W_lon % p->win_w != 0) return AERIS_ERR_NOT_DIVISIBLE;
+  if (p->shift_h < 0 || p->shift_h >= p->win_h || p->shift_w < 0 || p->shift_w >= p->win_w)
+    return AERIS_ERR_BAD_SHIFT;
+  if (p->mask_policy != AERIS_MASK_NONE && p->mask_policy != AERIS_MASK_LAT &&
+      p->mask_policy != AERIS_MASK_SWIN)
+    return AERIS_ERR_BAD_MASK;
+  if (p->out_dtype != AERIS_DT_BF16 && p->out_dtype != AERIS_DT_F32) return AERIS_ERR_BAD_DTYPE;
+  if ((long long)p->win_h * p->win_w > AERIS_MAX_WINDOW_TOKENS) return AERIS_ERR_WINDOW_TOO_LARGE;
+  if ((long long)p->H_lat * p->W_lon >= (1LL << 31)) return AERIS_ERR_INVALID_SHAPE;
+  if ((long long)p->B * p->heads * (p->H_lat / p->win_h) * (p->W_lon / p->win_w) *
+          (((long long)p->win_h * p->win_w + 127) / 128) >= (1LL << 31) - 8)
+    return AERIS_ERR_INVALID_SHAPE;
+  const long long d = p->head_dim;
+  s->qkv_head = p->qkv_head_stride ? p->qkv_head_stride : d;
+  s->o_head = p->o_head_stride ? p->o_head_stride : d;
+  s->qkv_tok = p->qkv_tok_stride ? p->qkv_tok_stride : (long long)p->heads * d;
+  s->o_tok = p->o_tok_stride ? p->o_tok_stride : (long long)p->heads * d;
+  if (s->qkv_head < d || s->o_head < d) return AERIS_ERR_INVALID_SHAPE;
+  if (s->qkv_tok < (p->heads - 1) * s->qkv_head + d) return AERIS_ERR_INVALID_SHAPE;
+  if (s->o_tok < (p->heads - 1) * s->o_head + d) return AERIS_ERR_INVALID_SHAPE;
+  if ((s->qkv_head | s->qkv_tok | s->o_head | s->o_tok) & 7) return AERIS_ERR_MISALIGNED;
+  return AERIS_OK;
+}
+
+aeris::KParams derive(const aeris_winattn_params* p, const Strides& s) {
+  aeris::KParams k;
+  k.B = p->B;
+  k.H = p->H_lat;
+  k.W = p->W_lon;
+  k.nh = p->heads;
+  k.ws_h = p->win_h;
+  k.ws_w = p->win_w;
+  k.s_h = p->shift_h;
+  k.s_w = p->shift_w;
+  k.mask = p->mask_policy;
+  k.nWy = p->H_lat / p->win_h;
+  k.nWx = p->W_lon / p->win_w;
+  k.T = p->win_h * p->win_w;
+  k.n_tiles = (k.T + aeris::kResident - 1) / aeris::kResident;
+  k.n_work = k.B * k.nWy * k.nWx * k.nh * k.n_tiles;
+  k.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.f / sqrtf((float)p->head_dim);
+  k.scale_log2 = k.scale * 1.4426950408889634f;
+  k.qkv_tok = s.qkv_tok;
+  k.qkv_head = s.qkv_head;
+  k.o_tok = s.o_tok;
+  k.o_head = s.o_head;
+  return k;
+}
+
+bool misaligned(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+int aeris_winattn_validate(const aeris_winattn_params* p) {
+  Strides s;
+  return resolve(p, &s);
+}
+
+int aeris_winattn_fwd(const aeris_winattn_params* p, const void* q, const void* k, const void* v,
+                      void* o, float* lse, void* hip_stream) {
+  Strides s;
+  const int rc = resolve(p, &s);
+  if (rc != AERIS_OK) return rc;
+  if (!q || !k || !v || !o || !lse) return AERIS_ERR_NULL_POINTER;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse))
+    return AERIS_ERR_MISALIGNED;
+  const aeris::KParams kp = derive(p, s);
+  if (aeris::launch_fwd(kp, p->head_dim, p->out_dtype == AERIS_DT_F32, q, k, v, o, lse,
+                        static_cast<hipStream_t>(hip_stream)) != 0)
+    return AERIS_ERR_HIP_LAUNCH;
+  return AERIS_OK;
+}
+
+size_t aeris_winattn_bwd_workspace_bytes(const aeris_winattn_params* p) {
+  Strides s;
+  if (resolve(p, &s) != AERIS_OK) return 0;
+  return (size_t)p->B * p->heads * p->H_lat * p->W_lon * sizeof(float);
+}
+
+int aeris_winattn_bwd(const aeris_winattn_params* p, const void* q, const void* k, const void* v,
+                      const void* o, const float* lse, const void* d_o, void* dq, void* dk,
+                      void* dv, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Strides s;
+  const int rc = resolve(p, &s);
+  if (rc != AERIS_OK) return rc;
+  if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !workspace)
+    return AERIS_ERR_NULL_POINTER;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) ||
+      misaligned(d_o) || misaligned(dq) || misaligned(dk) || misaligned(dv) ||
+      misaligned(workspace))
+    return AERIS_ERR_MISALIGNED;
+  if (workspace_bytes < aeris_winattn_bwd_workspace_bytes(p)) return AERIS_ERR_WORKSPACE_TOO_SMALL;
+  const aeris::KParams kp = derive(p, s);
+  if (aeris::launch_bwd(kp, p->head_dim, p->out_dtype == AERIS_DT_F32, q, k, v, o, lse, d_o, dq,
+                        dk, dv, static_cast<float*>(workspace),
+                        static_cast<hipStream_t>(hip_stream)) != 0)
+    return AERIS_ERR_HIP_LAUNCH;
+  return AERIS_OK;
+}
+
+const char* aeris_winattn_strerror(int code) {
+  switch (code) {
+    case AERIS_OK: return "ok";
+    case AERIS_ERR_NULL_POINTER: return "null pointer argument";
+    case AERIS_ERR_INVALID_SHAPE: return "invalid shape or stride";
+    case AERIS_ERR_NOT_DIVISIBLE: return "window does not divide the grid";
+    case AERIS_ERR_BAD_SHIFT: return "shift must satisfy 0 <= shift < window";
+    case AERIS_ERR_BAD_MASK: return "unknown mask policy";
+    case AERIS_ERR_UNSUPPORTED_HEAD_DIM: return "head_dim must be 32, 64 or 128";
+    case AERIS_ERR_MISALIGNED: return "pointer or stride not 16-byte aligned";
+    case AERIS_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case AERIS_ERR_WINDOW_TOO_LARGE: return "window has more tokens than AERIS_MAX_WINDOW_TOKENS";
+    case AERIS_ERR_BAD_DTYPE: return "unknown output dtype";
+    case AERIS_ERR_HIP_LAUNCH: return "HIP kernel launch failed";
+  }
+  return "unknown error code";
+}
+
+int aeris_winattn_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,275 @@
+// Shared device-side pieces of the gfx950 shifted-window attention kernels:
+// kernel parameter block, window geometry (cyclic shift + partition + region
+// ordering), MFMA operand types, tile staging through LDS.
+//
+// Window geometry follows the AERIS paper's Model Architecture section (square
+// windows, shifted on alternating layers) with the cyclic wrap of Fig. 2a; the
+// region/mask rules are the ones stated in include/aeris_winattn.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace aeris {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;      // 4 wavefronts of 64 lanes
+constexpr int kWaves = 4;
+constexpr int kResident = 128;     // tokens a workgroup keeps in registers (32 per wave)
+constexpr int kStream = 64;        // tokens per streamed LDS tile
+constexpr int kPad = 8;            // bf16 elements of padding per LDS row (16 bytes)
+constexpr float kLazyRescale = 8.0f;  // log2 units a row maximum may lag behind
+
+// Host-filled launch parameters (plain data, passed by value).
+struct KParams {
+  int B, H, W, nh;
+  int ws_h, ws_w, s_h, s_w;
+  int mask;            // AERIS_MASK_*
+  int nWy, nWx;        // windows along latitude / longitude
+  int T;               // tokens per window
+  int n_tiles;         // resident-side tiles per window = ceil(T / kResident)
+  int n_work;          // B * nWy * nWx * nh * n_tiles workgroups carry work
+  float scale;         // softmax scale
+  float scale_log2;    // scale * log2(e)
+  long long qkv_tok, qkv_head;  // element strides of q,k,v,dq,dk,dv
+  long long o_tok, o_head;      // element strides of o, dO
+};
+
+// ----------------------------------------------------------------------------
+// Workgroup id -> (pair, tile).  Hardware deals consecutive workgroup ids to
+// the eight XCDs in turn; this remap gives each XCD a contiguous range of
+// logical ids, so the tiles of one (batch, window, head) -- which all stream
+// the same K/V (or Q/dO) rows -- share one XCD's L2.
+// ----------------------------------------------------------------------------
+__device__ __forceinline__ int logical_block(int n_blocks_padded) {
+  const int per_xcd = n_blocks_padded >> 3;
+  const int id = blockIdx.x;
+  return (id & 7) * per_xcd + (id >> 3);
+}
+
+// One (batch, window, head) and how its tokens are enumerated.
+//
+// Tokens of a window are enumerated region by region (at most a 2x2 split of
+// the window by the seam rows/columns), row-major inside a region.  Attention
+// inside a window does not depend on the enumeration order, and with this one
+// every token's visible keys form one contiguous index range [lo, hi), so
+// masked blocks are skipped whole and the rest is masked by two compares.
+struct Window {
+  int b, head, wy, wx;
+  int split_r, split_c;   // first row / column of the second region (== side if no seam)
+  int wc0, wc1;           // columns in the left / right region
+  int s01, s10, s11, T;   // enumeration start of regions (0,1), (1,0), (1,1)
+
+  __device__ __forceinline__ void init(const KParams& p, int pair) {
+    head = pair % p.nh;
+    int w = pair / p.nh;
+    wx = w % p.nWx;
+    w /= p.nWx;
+    wy = w % p.nWy;
+    b = w / p.nWy;
+    const bool lat_seam = p.mask != 0 && wy == p.nWy - 1 && p.s_h > 0;
+    const bool lon_seam = p.mask == 2 && wx == p.nWx - 1 && p.s_w > 0;
+    split_r = lat_seam ? p.ws_h - p.s_h : p.ws_h;
+    split_c = lon_seam ? p.ws_w - p.s_w : p.ws_w;
+    wc0 = split_c;
+    wc1 = p.ws_w - split_c;
+    const int hr0 = split_r, hr1 = p.ws_h - split_r;
+    s01 = hr0 * wc0;
+    s10 = s01 + hr0 * wc1;
+    s11 = s10 + hr1 * wc0;
+    T = p.T;
+  }
+  // Visible key range of token t.
+  __device__ __forceinline__ void range(int t, int& lo, int& hi) const {
+    if (t < s01) { lo = 0; hi = s01; }
+    else if (t < s10) { lo = s01; hi = s10; }
+    else if (t < s11) { lo = s10; hi = s11; }
+    else { lo = s11; hi = T; }
+  }
+  // Grid point (row-major index y*W + x) of token t: partition + cyclic shift.
+  __device__ __forceinline__ int grid_index(const KParams& p, int t) const {
+    int lo, w, r0, c0;
+    if (t < s01) { lo = 0; w = wc0; r0 = 0; c0 = 0; }
+    else if (t < s10) { lo = s01; w = wc1; r0 = 0; c0 = split_c; }
+    else if (t < s11) { lo = s10; w = wc0; r0 = split_r; c0 = 0; }
+    else { lo = s11; w = wc1; r0 = split_r; c0 = split_c; }
+    const int u = t - lo;
+    const int rr = u / w;
+    const int cc = u - rr * w;
+    int y = wy * p.ws_h + r0 + rr + p.s_h;
+    int x = wx * p.ws_w + c0 + cc + p.s_w;
+    if (y >= p.H) y -= p.H;
+    if (x >= p.W) x -= p.W;
+    return y * p.W + x;
+  }
+};
+
+// Visible-range bookkeeping for the 128 resident tokens of a workgroup (32 per
+// wave, token `first + lane%32` per lane).  Tokens are enumerated region by
+// region, so range starts and ends are non-decreasing in the token index.
+struct Ranges {
+  int tok;            // this lane's resident token, clamped to T-1
+  bool valid;         // false for phantom tokens past the window's end
+  bool wave_active;   // wave owns at least one real token
+  int lo, hi;         // visible streamed tokens of this lane
+  int w_lo, w_hi;     // union over the wave (skip streamed blocks outside)
+  int lo_max, hi_min; // intersection over the wave (blocks inside need no mask)
+  int wg_lo, wg_hi;   // union over the workgroup (loop bounds)
+
+  __device__ __forceinline__ void init(const Window& win, int tile, int wave, int qi) {
+    const int T = win.T;
+    const int wave_t0 = tile * kResident + wave * 32;
+    wave_active = wave_t0 < T;
+    const int t = wave_t0 + qi;
+    valid = t < T;
+    tok = valid ? t : T - 1;
+    win.range(tok, lo, hi);
+    int unused;
+    const int wg_last = tile * kResident + kResident - 1;
+    win.range(tile * kResident, wg_lo, unused);
+    win.range(wg_last < T ? wg_last : T - 1, unused, wg_hi);
+    w_lo = w_hi = lo_max = hi_min = 0;
+    if (wave_active) {
+      const int last = wave_t0 + 31;
+      win.range(wave_t0, w_lo, hi_min);
+      win.range(last < T ? last : T - 1, lo_max, w_hi);
+    }
+  }
+  // Block [s, s+32) of streamed tokens: does this wave need it, and masked?
+  __device__ __forceinline__ bool skip(int s) const { return s + 32 <= w_lo || s >= w_hi; }
+  __device__ __forceinline__ bool mask_free(int s) const { return s >= lo_max && s + 32 <= hi_min; }
+};
+
+// Fill the per-window table token -> y*W + x (in LDS).  Caller barriers.
+__device__ __forceinline__ void build_token_table(const KParams& p, const Window& win,
+                                                  int* tok_grid) {
+  for (int t = threadIdx.x; t < p.T; t += kThreads) tok_grid[t] = win.grid_index(p, t);
+}
+
+// ----------------------------------------------------------------------------
+// MFMA wrappers.  v_mfma_f32_32x32x16_bf16: D[32x32] += A[32x16] * B[16x32].
+// Lane l supplies A[l%32][8*(l/32) .. +8] and B[8*(l/32) .. +8][l%32]; it
+// receives D[8*(v/4) + 4*(l/32) + v%4][l%32] in accumulator register v.
+// Because the eight contraction indices a lane supplies only have to agree
+// between A and B, a D tile can be fed back as the B operand of the next
+// product without any cross-lane movement: registers 8c..8c+7 of lane l hold
+// rows {16c + 4*(l/32) + (0..3), 16c + 8 + 4*(l/32) + (0..3)}, and the A
+// operand is fetched in that same row order (see transposed_pos()).
+// ----------------------------------------------------------------------------
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Row of a 32x32 accumulator tile held in register v by a lane of half g.
+__device__ __forceinline__ int acc_row(int v, int g) { return 8 * (v >> 2) + 4 * g + (v & 3); }
+
+// Position, inside a transposed LDS row, of streamed token kappa (multiple of
+// 4; four consecutive tokens stay adjacent).  Within each group of 16 tokens
+// the four 4-token granules are stored in the order 0,2,1,3 so that one
+// 16-byte read returns exactly the eight contraction rows a lane needs.
+__device__ __forceinline__ int transposed_pos(int kappa) {
+  const int gran = (kappa >> 2) & 3;
+  return (kappa & ~15) + 8 * (gran & 1) + 4 * (gran >> 1);
+}
+
+__device__ __forceinline__ float wave_half_max(float x) {
+  return fmaxf(x, __shfl_xor(x, 32));
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return *reinterpret_cast<uint32_t*>(&r);
+}
+
+// ----------------------------------------------------------------------------
+// Streamed tile staging: kStream tokens x D channels of one tensor go from
+// global memory to registers (16-byte loads, 4 tokens x 8 channels per work
+// item), then to LDS row-major [token][D + pad] and/or transposed
+// [channel][kStream + pad] with the token order of transposed_pos().
+// ----------------------------------------------------------------------------
+template <int D>
+struct Stage {
+  static constexpr int kChunks = D / 8;                    // 16-byte chunks per token row
+  static constexpr int kItems = (kStream / 4) * kChunks;   // work items per tile
+  static constexpr int kPerThread = (kItems + kThreads - 1) / kThreads;
+  static constexpr int kRowStride = D + kPad;              // row-major LDS row, elements
+  static constexpr int kTrStride = kStream + kPad;         // transposed LDS row, elements
+  static constexpr int kRowTile = kStream * kRowStride;    // elements
+  static constexpr int kTrTile = D * kTrStride;            // elements
+
+  u32x4 r[kPerThread][4];
+
+  // base: pointer to (batch, head) origin; tok_grid: LDS table; t0: first token.
+  __device__ __forceinline__ void load(const bf16_t* base, long long tok_stride,
+                                       const int* tok_grid, int t0, int T) {
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) {
+      const int item = threadIdx.x + j * kThreads;
+      if (kItems % kThreads != 0 && item >= kItems) break;
+      const int chunk = item % kChunks;
+      const int tg = item / kChunks;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int t = t0 + 4 * tg + i;
+        t = t < T ? t : T - 1;          // phantom tokens re-read the last one; masked later
+        const bf16_t* src = base + (long long)tok_grid[t] * tok_stride + chunk * 8;
+        r[j][i] = *reinterpret_cast<const u32x4*>(src);
+      }
+    }
+  }
+
+  __device__ __forceinline__ void store_rowmajor(bf16_t* tile) const {
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) {
+      const int item = threadIdx.x + j * kThreads;
+      if (kItems % kThreads != 0 && item >= kItems) break;
+      const int chunk = item % kChunks;
+      const int tg = item / kChunks;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<u32x4*>(tile + (4 * tg + i) * kRowStride + chunk * 8) = r[j][i];
+    }
+  }
+
+  __device__ __forceinline__ void store_transposed(bf16_t* tile) const {
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) {
+      const int item = threadIdx.x + j * kThreads;
+      if (kItems % kThreads != 0 && item >= kItems) break;
+      const int chunk = item % kChunks;
+      const int tg = item / kChunks;
+      const int pos = transposed_pos(4 * tg);
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        // dword w of each token row holds channels 2w (low half) and 2w+1 (high half)
+        const uint32_t a0 = r[j][0][w], a1 = r[j][1][w], a2 = r[j][2][w], a3 = r[j][3][w];
+        u32x2 even = {(a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16)};
+        u32x2 odd = {(a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u)};
+        bf16_t* row = tile + (chunk * 8 + 2 * w) * kTrStride + pos;
+        *reinterpret_cast<u32x2*>(row) = even;
+        *reinterpret_cast<u32x2*>(row + kTrStride) = odd;
+      }
+    }
+  }
+};
+
+// Output element stores: four consecutive channels of one token.
+__device__ __forceinline__ void store4(bf16_t* dst, float a, float b, float c, float d) {
+  u32x2 v = {pack_bf16(a, b), pack_bf16(c, d)};
+  *reinterpret_cast<u32x2*>(dst) = v;
+}
+__device__ __forceinline__ void store4(float* dst, float a, float b, float c, float d) {
+  f32x4 v = {a, b, c, d};
+  *reinterpret_cast<f32x4*>(dst) = v;
+}
+
+}  // namespace aeris

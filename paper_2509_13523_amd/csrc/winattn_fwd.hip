@@ -1,0 +1,198 @@
+// Forward shifted-window attention for gfx950 (AERIS paper, Model Architecture
+// section: window partition + shift, then dot-product attention per window and
+// head; computed flash-style: the T x T logits never leave the chip).
+//
+// One workgroup = 128 queries of one (batch, window, head); each of its four
+// wavefronts owns 32 queries, one per lane pair (l, l+32).  Keys/values stream
+// through LDS 64 tokens at a time.  The logits are produced transposed,
+//     S^T[key, query] = K Q^T        (A = K tile from LDS, B = Q in registers)
+// so every lane holds logits of ONE query: the softmax statistics are per-lane
+// scalars and the row reductions need a single cross-lane exchange.  P^T then
+// feeds the second product in place,
+//     O^T[channel, query] += V^T P^T (A = transposed V tile from LDS, B = P^T).
+#include "winattn_common.hpp"
+#include "winattn_launch.hpp"
+
+namespace aeris {
+
+template <int D, typename OutT>
+__global__ __launch_bounds__(kThreads, 1) void winattn_fwd_kernel(
+    KParams p, int n_blocks_padded, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+    const bf16_t* __restrict__ v, OutT* __restrict__ o, float* __restrict__ lse) {
+  using St = Stage<D>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  int* tok_grid = reinterpret_cast<int*>(smem);
+  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + ((p.T * 4 + 15) & ~15));
+  bf16_t* Vt = Ks + St::kRowTile;
+
+  const int logical = logical_block(n_blocks_padded);
+  if (logical >= p.n_work) return;
+  const int pair = logical / p.n_tiles;
+  const int qt = logical - pair * p.n_tiles;
+
+  Window win;
+  win.init(p, pair);
+  build_token_table(p, win, tok_grid);
+  __syncthreads();
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int qi = lane & 31, g = lane >> 5;
+  const int T = p.T;
+
+  const long long plane = (long long)p.H * p.W;
+  const bf16_t* qb = q + ((long long)win.b * plane) * p.qkv_tok + (long long)win.head * p.qkv_head;
+  const bf16_t* kb = k + ((long long)win.b * plane) * p.qkv_tok + (long long)win.head * p.qkv_head;
+  const bf16_t* vb = v + ((long long)win.b * plane) * p.qkv_tok + (long long)win.head * p.qkv_head;
+
+  // ---- this lane's query ----------------------------------------------------
+  Ranges rg;
+  rg.init(win, qt, wave, qi);
+  const bool wave_active = rg.wave_active;
+  const bool q_valid = rg.valid;
+  const int q_grid = tok_grid[rg.tok];
+  const int lo_q = rg.lo, hi_q = rg.hi;
+
+  bf16x8 qreg[D / 16];
+  {
+    const bf16_t* qrow = qb + (long long)q_grid * p.qkv_tok + 8 * g;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk)
+      qreg[kk] = *reinterpret_cast<const bf16x8*>(qrow + kk * 16);
+  }
+
+  f32x16 oacc[D / 32];
+#pragma unroll
+  for (int cb = 0; cb < D / 32; ++cb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) oacc[cb][i] = 0.f;
+  float m_run = -INFINITY;   // running (lagging) row maximum, log2 domain
+  float l_run = 0.f;         // this lane's share of the row sum
+
+  const int kt_begin = rg.wg_lo / kStream;
+  const int kt_end = (rg.wg_hi + kStream - 1) / kStream;
+
+  St kst, vst;
+  kst.load(kb, p.qkv_tok, tok_grid, kt_begin * kStream, T);
+  vst.load(vb, p.qkv_tok, tok_grid, kt_begin * kStream, T);
+
+  for (int kt = kt_begin; kt < kt_end; ++kt) {
+    if (kt != kt_begin) __syncthreads();          // everyone done reading the old tile
+    kst.store_rowmajor(Ks);
+    vst.store_transposed(Vt);
+    __syncthreads();
+    if (kt + 1 < kt_end) {                        // next tile flies during the math
+      kst.load(kb, p.qkv_tok, tok_grid, (kt + 1) * kStream, T);
+      vst.load(vb, p.qkv_tok, tok_grid, (kt + 1) * kStream, T);
+    }
+    const int tile_lo = kt * kStream;
+    if (!wave_active) continue;
+#pragma unroll
+    for (int kb2 = 0; kb2 < kStream / 32; ++kb2) {
+      const int sub_lo = tile_lo + kb2 * 32;
+      if (rg.skip(sub_lo)) continue;   // wave-uniform
+      // ---- S^T = K Q^T -------------------------------------------------------
+      f32x16 s;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[i] = 0.f;
+      const bf16_t* krow = Ks + (kb2 * 32 + qi) * St::kRowStride + 8 * g;
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk)
+        s = mfma32(*reinterpret_cast<const bf16x8*>(krow + kk * 16), qreg[kk], s);
+      // ---- mask --------------------------------------------------------------
+      if (!rg.mask_free(sub_lo)) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int kidx = sub_lo + acc_row(i, g);
+          if (kidx < lo_q || kidx >= hi_q) s[i] = -INFINITY;
+        }
+      }
+      // ---- online softmax (log2 domain, lagging maximum) ----------------------
+      float mx = s[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
+      mx = wave_half_max(mx) * p.scale_log2;
+      const bool grow = mx > m_run + kLazyRescale;
+      if (__any(grow)) {
+        const float alpha = grow ? __builtin_amdgcn_exp2f(m_run - mx) : 1.f;
+        m_run = grow ? mx : m_run;
+        l_run *= alpha;
+#pragma unroll
+        for (int cb = 0; cb < D / 32; ++cb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) oacc[cb][i] *= alpha;
+      }
+      const float m_sub = m_run == -INFINITY ? 0.f : m_run;
+      float pv[16];
+      float psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.scale_log2, -m_sub));
+        psum += pv[i];
+      }
+      l_run += psum;
+      // ---- O^T += V^T P^T ------------------------------------------------------
+      union { u32x4 u; bf16x8 h; } pb[2];
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pb[c].u[e] = pack_bf16(pv[8 * c + 2 * e], pv[8 * c + 2 * e + 1]);
+      const bf16_t* vrow = Vt + qi * St::kTrStride + kb2 * 32 + 8 * g;
+#pragma unroll
+      for (int cb = 0; cb < D / 32; ++cb)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+          oacc[cb] = mfma32(
+              *reinterpret_cast<const bf16x8*>(vrow + cb * 32 * St::kTrStride + 16 * c),
+              pb[c].h, oacc[cb]);
+    }
+  }
+
+  // ---- epilogue: normalise, un-shift/un-partition store -----------------------
+  if (!q_valid) return;
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float inv = 1.f / l_tot;
+  OutT* orow = o + ((long long)win.b * plane + q_grid) * p.o_tok + (long long)win.head * p.o_head;
+#pragma unroll
+  for (int cb = 0; cb < D / 32; ++cb)
+#pragma unroll
+    for (int vq = 0; vq < 4; ++vq)
+      store4(orow + cb * 32 + 8 * vq + 4 * g, oacc[cb][4 * vq] * inv, oacc[cb][4 * vq + 1] * inv,
+             oacc[cb][4 * vq + 2] * inv, oacc[cb][4 * vq + 3] * inv);
+  if (g == 0)
+    lse[((long long)win.b * p.nh + win.head) * plane + q_grid] =
+        (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+}
+
+template <int D, typename OutT>
+static int launch_fwd_t(const KParams& kp, const void* q, const void* k, const void* v, void* o,
+                        float* lse, hipStream_t stream) {
+  using St = Stage<D>;
+  const int n_blocks = (kp.n_work + 7) & ~7;
+  const size_t smem = ((kp.T * 4 + 15) & ~15) + (St::kRowTile + St::kTrTile) * sizeof(bf16_t);
+  auto kern = winattn_fwd_kernel<D, OutT>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+    return -1;
+  hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, n_blocks,
+                     static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
+                     static_cast<const bf16_t*>(v), static_cast<OutT*>(o), lse);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_fwd(const KParams& kp, int head_dim, bool out_f32, const void* q, const void* k,
+               const void* v, void* o, float* lse, hipStream_t stream) {
+#define AERIS_FWD_CASE(DD)                                                             \
+  case DD:                                                                             \
+    return out_f32 ? launch_fwd_t<DD, float>(kp, q, k, v, o, lse, stream)              \
+                   : launch_fwd_t<DD, bf16_t>(kp, q, k, v, o, lse, stream);
+  switch (head_dim) {
+    AERIS_FWD_CASE(32)
+    AERIS_FWD_CASE(64)
+    AERIS_FWD_CASE(128)
+  }
+#undef AERIS_FWD_CASE
+  return -1;
+}
+
+}  // namespace aeris

@@ -1,0 +1,16 @@
+// Host-side launchers implemented next to their kernels.  Each returns 0 when
+// the launches were enqueued and -1 when HIP reported a launch error.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "winattn_common.hpp"
+
+namespace aeris {
+
+int launch_fwd(const KParams& kp, int head_dim, bool out_f32, const void* q, const void* k,
+               const void* v, void* o, float* lse, hipStream_t stream);
+
+int launch_bwd(const KParams& kp, int head_dim, bool out_f32, const void* q, const void* k,
+               const void* v, const void* o, const float* lse, const void* d_o, void* dq,
+               void* dk, void* dv, float* delta, hipStream_t stream);
+
+}  // namespace aeris
