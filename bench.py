@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark: shifted-window attention forward+backward on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch: for every
+layer of the workload (an unshifted and a half-window-shifted attention layer
+alternate in the AERIS Swin stack) the forward kernel, then the delta, dK/dV
+and dQ kernels.  Inputs are generated on the device before the clock starts.
+
+Prints ONE JSON line.  `value` is model TFLOP/s: 4*d*U forward + 8*d*U backward
+per layer, U = unmasked (query, key) pairs; recomputation inside the backward
+kernels (18*d*U are executed in total) is not credited.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+WORKLOADS = {
+    # diffusion-ensemble batch on the 0.25-degree grid: the headline workload
+    "c5": dict(shape=(4, 720, 1440, 16, 128), win=(60, 60), layers=[(0, 0), (30, 30)],
+               mask=2, kind="blend", sigmas=[0.1, 0.5, 1.0, 2.0], bwd=True, seed=5000,
+               name="B=4 x 720x1440 grid, 16 heads x 128, 60x60 windows, shift 0/30, SWIN mask"),
+    # one GPU's share of a large-model layer
+    "c4": dict(shape=(1, 120, 1440, 24, 128), win=(60, 60), layers=[(30, 30)], mask=2,
+               kind="blend", sigmas=None, bwd=True, seed=4000,
+               name="48 windows 60x60 (2x24 band), 24 heads x 128, shift 30, SWIN mask"),
+    "c3": dict(shape=(1, 720, 1440, 16, 64), win=(60, 60), layers=[(30, 30)], mask=2,
+               kind="normal", sigmas=None, bwd=False, seed=3000,
+               name="720x1440 grid, 16 heads x 64, 60x60 windows, shift 30, forward only"),
+}
+
+# HBM traffic of the dominant kernel per launch, bytes, from rocprofv3 --pmc runs
+# (FETCH_SIZE and WRITE_SIZE scaled by a copy kernel of known size); see profiles/.
+MEASURED_TRAFFIC = {}
+
+
+def unmasked_pairs(H, W, win, shift, mask):
+    """Closed form of the oracle's pair count (per batch member and head)."""
+    def axis(L, ws, s, masked):
+        n = L // ws
+        if not masked or s == 0:
+            return float(n)
+        return (n - 1) + ((ws - s) ** 2 + s ** 2) / ws ** 2
+    fy = axis(H, win[0], shift[0], mask in (1, 2))
+    fx = axis(W, win[1], shift[1], mask == 2)
+    return fy * fx * (win[0] * win[1]) ** 2
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-pairs", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (pairs of (batch, window, head) are "
+                 "independent, so more GPUs would each run this same kernel on their share); "
+                 "--gpus %d is not supported" % args.gpus)
+
+    import numpy as np
+    import torch
+    from paper_2509_13523_amd import binding as B
+    from paper_2509_13523_amd import synth
+
+    B.load()   # fails loudly if the HIP library is not built
+    wl = WORKLOADS[args.workload]
+    shape, win, mask = wl["shape"], wl["win"], wl["mask"]
+    Bn, H, W, nh, d = shape
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    n_in = 4 if wl["bwd"] else 3
+    tensors = synth.make_inputs_device(wl["kind"], wl["seed"], shape, n_in, sigmas=wl["sigmas"],
+                                       device=dev)
+    tq, tk, tv = tensors[:3]
+    tdo = tensors[3] if wl["bwd"] else None
+    o = torch.empty_like(tq)
+    lse = torch.empty((Bn, nh, H, W), dtype=torch.float32, device=dev)
+    if wl["bwd"]:
+        dq, dk, dv = torch.empty_like(tq), torch.empty_like(tq), torch.empty_like(tq)
+        p0 = B.make_params(shape, win, (0, 0), mask)
+        ws = torch.empty(B.aeris_winattn_bwd_workspace_bytes(p0), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    U = {s: Bn * nh * unmasked_pairs(H, W, win, s, mask) for s in wl["layers"]}
+    model_flops = sum((12 if wl["bwd"] else 4) * d * U[s] for s in wl["layers"])
+    kernel_flops = {"fwd": 4, "dq": 6, "dkdv": 8, "delta": 0}
+    events = {k: [] for k in kernel_flops}
+
+    def timed(name, fn, record):
+        if not record:
+            fn()
+            return
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        events[name].append((e0, e1))
+
+    def step(record):
+        for s in wl["layers"]:
+            timed("fwd", lambda: B.aeris_winattn_fwd(tq, tk, tv, win, s, mask, o=o, lse=lse),
+                  record)
+            if wl["bwd"]:
+                for name, st in (("delta", B.AERIS_BWD_DELTA), ("dkdv", B.AERIS_BWD_DKDV),
+                                 ("dq", B.AERIS_BWD_DQ)):
+                    timed(name, lambda: B.aeris_winattn_bwd_stages(
+                        tq, tk, tv, o, lse, tdo, win, s, mask, dq=dq, dk=dk, dv=dv,
+                        workspace=ws, stages=st), record)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = model_flops / (ms_per_step * 1e-3) / 1e12
+
+    kern = {}
+    for name, evs in events.items():
+        if evs:
+            ms = sum(a.elapsed_time(b) for a, b in evs) / len(evs)
+            kern[name] = {"avg_ms": round(ms, 4), "launches": len(evs)}
+            if kernel_flops[name]:
+                fl = kernel_flops[name] * d * sum(U.values()) / len(U)
+                kern[name]["tflops_executed"] = round(fl / (ms * 1e-3) / 1e12, 2)
+    dom = max((k for k in kern if kernel_flops[k]), key=lambda k: kern[k]["avg_ms"] * len(events[k]))
+    dom_flops = kernel_flops[dom] * d * sum(U.values()) / len(U)
+    achieved = dom_flops / (kern[dom]["avg_ms"] * 1e-3) / 1e12
+    roofline = {"kernel": "winattn_%s_kernel" % dom, "bound": "mfma", "achieved": round(achieved, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": MEASURED_TRAFFIC.get((args.workload, dom))}
+
+    out = {"metric": "window-attn fwd+bwd TFLOP/s (model FLOPs) and % bf16 MFMA peak, "
+                     "720x1440 grid, 60x60 win",
+           "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic", "pct_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
+           "config": {"workload": "%s: %s" % (args.workload, wl["name"]),
+                      "passes": "fwd+bwd" if wl["bwd"] else "fwd",
+                      "layers_per_step": len(wl["layers"]),
+                      "model_tflop_per_step": round(model_flops / 1e12, 2)},
+           "kernels": kern, "roofline": roofline}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, tq, tk, tv, tdo, args.cpu_pairs)
+    print(json.dumps(out))
+
+
+def cpu_baseline(wl, tq, tk, tv, tdo, n_pairs):
+    """The fp64 oracle, untouched, timed on a bounded sample of (batch, window, head)
+    pairs of this workload; reported in the metric's unit (model TFLOP/s)."""
+    import numpy as np
+    from oracle import winattn_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([t.get("num_threads", 1) for t in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    Bn, H, W, nh, d = wl["shape"]
+    win, mask = wl["win"], wl["mask"]
+    shift = wl["layers"][-1]
+    scale = 1.0 / np.sqrt(d)
+    nwy, nwx = H // win[0], W // win[1]
+    rng = np.random.default_rng(0)
+    flops, secs = 0.0, 0.0
+    picks = [(0, 0, 0, 0), (Bn - 1, nwy - 1, nwx - 1, nh - 1), (0, nwy - 1, 1, 1), (0, 0, nwx - 1, 2)]
+    while len(picks) < n_pairs:
+        picks.append((int(rng.integers(Bn)), int(rng.integers(nwy)), int(rng.integers(nwx)),
+                      int(rng.integers(nh))))
+    for (b, wy, wx, h) in picks[:n_pairs]:
+        y, x, yh, xh = orc.window_tokens(H, W, win, shift, wy, wx)
+        reg = orc.token_regions(H, W, win, shift, mask, yh, xh)
+        g = lambda t: t[b, :, :, h, :][y, x].float().cpu().numpy().astype(np.float64)
+        qw, kw, vw = g(tq), g(tk), g(tv)
+        dow = g(tdo) if tdo is not None else None
+        t0 = time.perf_counter()
+        orc.window_pair_fwd(qw, kw, vw, reg, scale)
+        if dow is not None:
+            orc.window_pair_bwd(qw, kw, vw, dow, reg, scale)
+        secs += time.perf_counter() - t0
+        pairs = float((reg[:, None] == reg[None, :]).sum())
+        flops += (12 if dow is not None else 4) * d * pairs
+    return {"value": round(flops / secs / 1e12, 5), "unit": "TFLOP/s", "cores": int(threads),
+            "kind": "oracle",
+            "sample": "%d (batch, window, head) pairs of the workload (interior, seam and corner "
+                      "windows), fwd%s, %.1f s of CPU time" %
+                      (n_pairs, "+bwd" if tdo is not None else "", secs)}
+
+
+if __name__ == "__main__":
+    main()

@@ -107,7 +107,8 @@ size_t aeris_winattn_bwd_workspace_bytes(const aeris_winattn_params* p);
  * Backward ("forward and backward pass with BF16 activations", Software
  * Environment section; formulas above).  Recomputes P from the saved LSE.
  *   q, k, v     : as in the forward call, read-only
- *   o, lse      : the forward outputs (o must have been written as bf16), read-only
+ *   o, lse      : the forward outputs (o in out_dtype, as the forward call with the
+ *                 same parameter block wrote it), read-only
  *   d_o         : bf16, layout of o, read-only
  *   dq, dk, dv  : out_dtype, layout of q/k/v, overwritten
  *   workspace   : >= aeris_winattn_bwd_workspace_bytes(p) bytes, 16-byte aligned,
@@ -118,6 +119,18 @@ int aeris_winattn_bwd(const aeris_winattn_params* p, const void* q, const void* 
                       const void* v, const void* o, const float* lse, const void* d_o,
                       void* dq, void* dk, void* dv, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
+
+/* The backward pass is three kernels; this variant runs a subset, in the order
+ * delta, dq, dkdv (for profiling one kernel, or to put dq and dkdv on different
+ * streams).  AERIS_BWD_DQ and AERIS_BWD_DKDV read the delta vector in
+ * `workspace`, so AERIS_BWD_DELTA must have completed on it first.  Outputs of
+ * stages that are not selected are left untouched.  stages == AERIS_BWD_ALL is
+ * aeris_winattn_bwd. */
+enum { AERIS_BWD_DELTA = 1, AERIS_BWD_DQ = 2, AERIS_BWD_DKDV = 4, AERIS_BWD_ALL = 7 };
+int aeris_winattn_bwd_stages(const aeris_winattn_params* p, const void* q, const void* k,
+                             const void* v, const void* o, const float* lse, const void* d_o,
+                             void* dq, void* dk, void* dv, void* workspace,
+                             size_t workspace_bytes, void* hip_stream, unsigned stages);
 
 /* Checks a parameter block without launching (host only): AERIS_OK or an error. */
 int aeris_winattn_validate(const aeris_winattn_params* p);

@@ -12,8 +12,10 @@ LIB_PATH = os.path.join(_HERE, "libaeris_winattn.so")
 
 AERIS_MASK_NONE, AERIS_MASK_LAT, AERIS_MASK_SWIN = 0, 1, 2
 AERIS_DT_BF16, AERIS_DT_F32 = 0, 1
+AERIS_BWD_DELTA, AERIS_BWD_DQ, AERIS_BWD_DKDV, AERIS_BWD_ALL = 1, 2, 4, 7
 
-EXPORTS = ("aeris_winattn_fwd", "aeris_winattn_bwd", "aeris_winattn_bwd_workspace_bytes",
+EXPORTS = ("aeris_winattn_fwd", "aeris_winattn_bwd", "aeris_winattn_bwd_stages",
+           "aeris_winattn_bwd_workspace_bytes",
            "aeris_winattn_validate", "aeris_winattn_strerror", "aeris_winattn_version")
 
 
@@ -54,6 +56,9 @@ def load():
     lib.aeris_winattn_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                       ctypes.c_size_t, vp]
     lib.aeris_winattn_bwd.restype = ctypes.c_int
+    lib.aeris_winattn_bwd_stages.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                             ctypes.c_size_t, vp, ctypes.c_uint]
+    lib.aeris_winattn_bwd_stages.restype = ctypes.c_int
     lib.aeris_winattn_bwd_workspace_bytes.argtypes = [P]
     lib.aeris_winattn_bwd_workspace_bytes.restype = ctypes.c_size_t
     lib.aeris_winattn_validate.argtypes = [P]
@@ -123,6 +128,14 @@ def aeris_winattn_fwd(q, k, v, win, shift, mask=AERIS_MASK_NONE, scale=None,
 def aeris_winattn_bwd(q, k, v, o, lse, d_o, win, shift, mask=AERIS_MASK_NONE, scale=None,
                       out_dtype=AERIS_DT_BF16, dq=None, dk=None, dv=None, workspace=None):
     """Returns (dq, dk, dv).  o must be the forward output in ``out_dtype``."""
+    return aeris_winattn_bwd_stages(q, k, v, o, lse, d_o, win, shift, mask, scale, out_dtype,
+                                    dq, dk, dv, workspace, AERIS_BWD_ALL)
+
+
+def aeris_winattn_bwd_stages(q, k, v, o, lse, d_o, win, shift, mask=AERIS_MASK_NONE, scale=None,
+                             out_dtype=AERIS_DT_BF16, dq=None, dk=None, dv=None, workspace=None,
+                             stages=AERIS_BWD_ALL):
+    """Subset of the backward kernels (see the header); returns (dq, dk, dv)."""
     import torch
     p = make_params(q.shape, win, shift, mask, scale, out_dtype)
     odt = _torch_out_dtype(out_dtype)
@@ -138,10 +151,14 @@ def aeris_winattn_bwd(q, k, v, o, lse, d_o, win, shift, mask=AERIS_MASK_NONE, sc
     need = aeris_winattn_bwd_workspace_bytes(p)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
-    rc = load().aeris_winattn_bwd(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(),
-                                  o.data_ptr(), lse.data_ptr(), d_o.data_ptr(), dq.data_ptr(),
-                                  dk.data_ptr(), dv.data_ptr(), workspace.data_ptr(),
-                                  workspace.numel() * workspace.element_size(), _stream())
+    lib = load()
+    args = (ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+            lse.data_ptr(), d_o.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
+            workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream())
+    if stages == AERIS_BWD_ALL:
+        rc = lib.aeris_winattn_bwd(*args)
+    else:
+        rc = lib.aeris_winattn_bwd_stages(*args, stages)
     if rc != 0:
         raise AerisError(rc, "aeris_winattn_bwd")
     return dq, dk, dv

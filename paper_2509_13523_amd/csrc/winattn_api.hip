@@ -59,7 +59,7 @@ aeris::KParams derive(const aeris_winattn_params* p, const Strides& s) {
   k.nWx = p->W_lon / p->win_w;
   k.T = p->win_h * p->win_w;
   k.n_tiles = (k.T + aeris::kResident - 1) / aeris::kResident;
-  k.n_work = k.B * k.nWy * k.nWx * k.nh * k.n_tiles;
+  k.n_pairs = k.B * k.nWy * k.nWx * k.nh;
   k.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.f / sqrtf((float)p->head_dim);
   k.scale_log2 = k.scale * 1.4426950408889634f;
   k.qkv_tok = s.qkv_tok;
@@ -104,6 +104,14 @@ size_t aeris_winattn_bwd_workspace_bytes(const aeris_winattn_params* p) {
 int aeris_winattn_bwd(const aeris_winattn_params* p, const void* q, const void* k, const void* v,
                       const void* o, const float* lse, const void* d_o, void* dq, void* dk,
                       void* dv, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return aeris_winattn_bwd_stages(p, q, k, v, o, lse, d_o, dq, dk, dv, workspace, workspace_bytes,
+                                  hip_stream, AERIS_BWD_ALL);
+}
+
+int aeris_winattn_bwd_stages(const aeris_winattn_params* p, const void* q, const void* k,
+                             const void* v, const void* o, const float* lse, const void* d_o,
+                             void* dq, void* dk, void* dv, void* workspace,
+                             size_t workspace_bytes, void* hip_stream, unsigned stages) {
   Strides s;
   const int rc = resolve(p, &s);
   if (rc != AERIS_OK) return rc;
@@ -117,7 +125,7 @@ int aeris_winattn_bwd(const aeris_winattn_params* p, const void* q, const void* 
   const aeris::KParams kp = derive(p, s);
   if (aeris::launch_bwd(kp, p->head_dim, p->out_dtype == AERIS_DT_F32, q, k, v, o, lse, d_o, dq,
                         dk, dv, static_cast<float*>(workspace),
-                        static_cast<hipStream_t>(hip_stream)) != 0)
+                        static_cast<hipStream_t>(hip_stream), stages & AERIS_BWD_ALL) != 0)
     return AERIS_ERR_HIP_LAUNCH;
   return AERIS_OK;
 }

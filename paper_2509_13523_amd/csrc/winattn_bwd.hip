@@ -69,8 +69,8 @@ __global__ __launch_bounds__(kThreads) void winattn_delta_kernel(
 // dQ: same skeleton as the forward kernel.
 // ----------------------------------------------------------------------------
 template <int D, typename OutT>
-__global__ __launch_bounds__(kThreads, 1) void winattn_dq_kernel(
-    KParams p, int n_blocks_padded, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+__global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
+    KParams p, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
     const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o, const float* __restrict__ lse,
     const float* __restrict__ delta, OutT* __restrict__ dq) {
   using St = Stage<D>;
@@ -80,10 +80,8 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dq_kernel(
   bf16_t* Vs = Ks + St::kRowTile;
   bf16_t* Kt = Vs + St::kRowTile;
 
-  const int logical = logical_block(n_blocks_padded);
-  if (logical >= p.n_work) return;
-  const int pair = logical / p.n_tiles;
-  const int qt = logical - pair * p.n_tiles;
+  int pair, qt;
+  if (!block_to_work(p, pair, qt)) return;
 
   Window win;
   win.init(p, pair);
@@ -91,7 +89,7 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dq_kernel(
   __syncthreads();
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qi = lane & 31, g = lane >> 5;
   const int T = p.T;
   const long long plane = (long long)p.H * p.W;
@@ -201,7 +199,7 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dq_kernel(
 // ----------------------------------------------------------------------------
 template <int D, typename OutT>
 __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
-    KParams p, int n_blocks_padded, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+    KParams p, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
     const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o, const float* __restrict__ lse,
     const float* __restrict__ delta, OutT* __restrict__ dk, OutT* __restrict__ dv) {
   using St = Stage<D>;
@@ -213,10 +211,8 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
   bf16_t* Qt = dOs + St::kRowTile;
   bf16_t* dOt = Qt + St::kTrTile;
 
-  const int logical = logical_block(n_blocks_padded);
-  if (logical >= p.n_work) return;
-  const int pair = logical / p.n_tiles;
-  const int kt = logical - pair * p.n_tiles;
+  int pair, kt;
+  if (!block_to_work(p, pair, kt)) return;
 
   Window win;
   win.init(p, pair);
@@ -224,7 +220,7 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
   __syncthreads();
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ki = lane & 31, g = lane >> 5;
   const int T = p.T;
   const long long plane = (long long)p.H * p.W;
@@ -362,7 +358,7 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
 template <int D, typename OutT>
 static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const void* v,
                         const void* o, const float* lse, const void* d_o, void* dq, void* dk,
-                        void* dv, float* delta, hipStream_t stream) {
+                        void* dv, float* delta, hipStream_t stream, unsigned stages) {
   using St = Stage<D>;
   const bf16_t* qp = static_cast<const bf16_t*>(q);
   const bf16_t* kp_ = static_cast<const bf16_t*>(k);
@@ -373,30 +369,32 @@ static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const v
   const long long n_thr = n_items * (D / 8);
   long long dblocks = (n_thr + kThreads - 1) / kThreads;
   if (dblocks > 256 * 64) dblocks = 256 * 64;
-  hipLaunchKernelGGL((winattn_delta_kernel<D, OutT>), dim3((unsigned)dblocks), dim3(kThreads), 0,
-                     stream, kp, n_items, static_cast<const OutT*>(o), dop, delta);
-  if (hipGetLastError() != hipSuccess) return -1;
+  if (stages & 1u) {
+    hipLaunchKernelGGL((winattn_delta_kernel<D, OutT>), dim3((unsigned)dblocks), dim3(kThreads),
+                       0, stream, kp, n_items, static_cast<const OutT*>(o), dop, delta);
+    if (hipGetLastError() != hipSuccess) return -1;
+  }
 
-  const int n_blocks = (kp.n_work + 7) & ~7;
+  const int n_blocks = grid_blocks(kp);
   const size_t tab = (kp.T * 4 + 15) & ~15;
-  {
+  if (stages & 2u) {
     const size_t smem = tab + (2 * St::kRowTile + St::kTrTile) * sizeof(bf16_t);
     auto kern = winattn_dq_kernel<D, OutT>;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return -1;
-    hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, n_blocks, qp, kp_,
+    hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, qp, kp_,
                        vp, dop, lse, static_cast<const float*>(delta), static_cast<OutT*>(dq));
     if (hipGetLastError() != hipSuccess) return -1;
   }
-  {
+  if (stages & 4u) {
     const size_t smem = tab + 2 * kStream * sizeof(float) +
                         (2 * St::kRowTile + 2 * St::kTrTile) * sizeof(bf16_t);
     auto kern = winattn_dkdv_kernel<D, OutT>;
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return -1;
-    hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, n_blocks, qp, kp_,
+    hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, qp, kp_,
                        vp, dop, lse, static_cast<const float*>(delta), static_cast<OutT*>(dk),
                        static_cast<OutT*>(dv));
     if (hipGetLastError() != hipSuccess) return -1;
@@ -406,12 +404,14 @@ static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const v
 
 int launch_bwd(const KParams& kp, int head_dim, bool out_f32, const void* q, const void* k,
                const void* v, const void* o, const float* lse, const void* d_o, void* dq,
-               void* dk, void* dv, float* delta, hipStream_t stream) {
+               void* dk, void* dv, float* delta, hipStream_t stream, unsigned stages) {
 #define AERIS_BWD_CASE(DD)                                                                     \
   case DD:                                                                                     \
     return out_f32                                                                             \
-               ? launch_bwd_t<DD, float>(kp, q, k, v, o, lse, d_o, dq, dk, dv, delta, stream)  \
-               : launch_bwd_t<DD, bf16_t>(kp, q, k, v, o, lse, d_o, dq, dk, dv, delta, stream);
+               ? launch_bwd_t<DD, float>(kp, q, k, v, o, lse, d_o, dq, dk, dv, delta, stream,  \
+                                         stages)                                        \
+               : launch_bwd_t<DD, bf16_t>(kp, q, k, v, o, lse, d_o, dq, dk, dv, delta, stream,  \
+                                          stages);
   switch (head_dim) {
     AERIS_BWD_CASE(32)
     AERIS_BWD_CASE(64)

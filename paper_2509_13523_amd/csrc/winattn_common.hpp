@@ -36,7 +36,7 @@ struct KParams {
   int nWy, nWx;        // windows along latitude / longitude
   int T;               // tokens per window
   int n_tiles;         // resident-side tiles per window = ceil(T / kResident)
-  int n_work;          // B * nWy * nWx * nh * n_tiles workgroups carry work
+  int n_pairs;         // B * nWy * nWx * nh
   float scale;         // softmax scale
   float scale_log2;    // scale * log2(e)
   long long qkv_tok, qkv_head;  // element strides of q,k,v,dq,dk,dv
@@ -45,14 +45,22 @@ struct KParams {
 
 // ----------------------------------------------------------------------------
 // Workgroup id -> (pair, tile).  Hardware deals consecutive workgroup ids to
-// the eight XCDs in turn; this remap gives each XCD a contiguous range of
-// logical ids, so the tiles of one (batch, window, head) -- which all stream
-// the same K/V (or Q/dO) rows -- share one XCD's L2.
+// the eight XCDs in turn.  Pairs (batch, window, head) are dealt to XCDs
+// round-robin (pair % 8), which balances seam windows -- they carry less work
+// -- across XCDs, and all tiles of one pair run on that one XCD, so the K/V
+// (or Q/dO) rows they all stream are shared through its L2.
+// Grid size: 8 * ceil(n_pairs / 8) * n_tiles.  Returns false for padding.
 // ----------------------------------------------------------------------------
-__device__ __forceinline__ int logical_block(int n_blocks_padded) {
-  const int per_xcd = n_blocks_padded >> 3;
+__device__ __forceinline__ bool block_to_work(const KParams& p, int& pair, int& tile) {
   const int id = blockIdx.x;
-  return (id & 7) * per_xcd + (id >> 3);
+  const int xcd = id & 7, slot = id >> 3;
+  const int pair_local = slot / p.n_tiles;
+  tile = slot - pair_local * p.n_tiles;
+  pair = pair_local * 8 + xcd;
+  return pair < p.n_pairs;
+}
+__host__ __device__ inline int grid_blocks(const KParams& p) {
+  return 8 * ((p.n_pairs + 7) / 8) * p.n_tiles;
 }
 
 // One (batch, window, head) and how its tokens are enumerated.

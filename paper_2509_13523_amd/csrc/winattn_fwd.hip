@@ -16,8 +16,8 @@
 namespace aeris {
 
 template <int D, typename OutT>
-__global__ __launch_bounds__(kThreads, 1) void winattn_fwd_kernel(
-    KParams p, int n_blocks_padded, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+__global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
+    KParams p, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
     const bf16_t* __restrict__ v, OutT* __restrict__ o, float* __restrict__ lse) {
   using St = Stage<D>;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -25,10 +25,8 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_fwd_kernel(
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + ((p.T * 4 + 15) & ~15));
   bf16_t* Vt = Ks + St::kRowTile;
 
-  const int logical = logical_block(n_blocks_padded);
-  if (logical >= p.n_work) return;
-  const int pair = logical / p.n_tiles;
-  const int qt = logical - pair * p.n_tiles;
+  int pair, qt;
+  if (!block_to_work(p, pair, qt)) return;
 
   Window win;
   win.init(p, pair);
@@ -36,7 +34,7 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_fwd_kernel(
   __syncthreads();
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qi = lane & 31, g = lane >> 5;
   const int T = p.T;
 
@@ -113,7 +111,7 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_fwd_kernel(
       for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
       mx = wave_half_max(mx) * p.scale_log2;
       const bool grow = mx > m_run + kLazyRescale;
-      if (__any(grow)) {
+      if (__builtin_expect(__any(grow), 0)) {
         const float alpha = grow ? __builtin_amdgcn_exp2f(m_run - mx) : 1.f;
         m_run = grow ? mx : m_run;
         l_run *= alpha;
@@ -168,13 +166,13 @@ template <int D, typename OutT>
 static int launch_fwd_t(const KParams& kp, const void* q, const void* k, const void* v, void* o,
                         float* lse, hipStream_t stream) {
   using St = Stage<D>;
-  const int n_blocks = (kp.n_work + 7) & ~7;
+  const int n_blocks = grid_blocks(kp);
   const size_t smem = ((kp.T * 4 + 15) & ~15) + (St::kRowTile + St::kTrTile) * sizeof(bf16_t);
   auto kern = winattn_fwd_kernel<D, OutT>;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
     return -1;
-  hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, n_blocks,
+  hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp,
                      static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
                      static_cast<const bf16_t*>(v), static_cast<OutT*>(o), lse);
   return hipGetLastError() == hipSuccess ? 0 : -1;

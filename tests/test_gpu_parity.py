@@ -1,0 +1,298 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 oracle.
+
+Tolerances (bf16 operands, fp32 accumulation): relative L2 <= 5e-3 and
+max-abs <= 2e-2 on O, dQ, dK, dV; |LSE error| <= 1e-2.  With bf16 outputs the
+rounding of the stored value alone is |x| * 2^-9, which exceeds 2e-2 once
+|x| >= 8, so there the max-abs bound is applied to the error in excess of that
+half-ulp; the fp32-output run of the same kernels is held to the plain bound.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import winattn_oracle as orc
+from paper_2509_13523_amd import binding as B
+from paper_2509_13523_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+REL_L2, MAX_ABS, LSE_ABS = 5e-3, 2e-2, 1e-2
+POLICIES = [B.AERIS_MASK_NONE, B.AERIS_MASK_LAT, B.AERIS_MASK_SWIN]
+
+
+def to_dev(bits):
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def to_f64(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def check(name, got, ref, bf16_out):
+    got = to_f64(got) if isinstance(got, torch.Tensor) else got
+    assert np.isfinite(got).all(), name
+    # a one-token window has dQ = dK = 0 exactly: allow an absolute floor of 1e-5 per element
+    rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 2e-3 * np.sqrt(ref.size))
+    err = np.abs(got - ref)
+    if bf16_out:
+        err = np.maximum(err - np.abs(ref) * 2.0 ** -9, 0.0) if np.abs(ref).max() >= 8 else err
+    assert rel <= REL_L2, "%s rel_l2 %.3e" % (name, rel)
+    assert err.max() <= MAX_ABS, "%s max_abs %.3e" % (name, err.max())
+
+
+def handover_bounds(qw, kw, vw, dow, reg, scale):
+    """First-order bounds on the change of dQ, dK of one (batch, window, head) when
+    delta = sum_c dO*O is formed from O stored in bf16 (one ulp, 2^-8 relative, per
+    element): |d dQ_i| <= scale e_i |sum_j P_ij K_j|, |d dK_j| <= scale sum_i P_ij e_i |Q_i|,
+    e_i = 2^-8 sum_c |dO_ic||O_ic|.  P and O come from the oracle."""
+    O, _, P = orc.window_pair_fwd(qw, kw, vw, reg, scale)
+    e = 2.0 ** -8 * (np.abs(dow) * np.abs(O)).sum(axis=1)
+    return scale * e[:, None] * np.abs(P @ kw), scale * (P * e[:, None]).T @ np.abs(qw)
+
+
+def check_with_bound(name, got, ref, bound):
+    err = np.abs(got - ref)
+    assert np.isfinite(got).all(), name
+    excess = np.maximum(err - bound - np.abs(ref) * 2.0 ** -9, 0.0)
+    assert excess.max() <= MAX_ABS, "%s max_abs excess %.3e" % (name, excess.max())
+    assert np.linalg.norm(err) <= REL_L2 * np.linalg.norm(ref) + np.linalg.norm(bound), name
+
+
+def run_case(shape, win, shift, mask, kind="normal", seed=1, bwd=True, scale=None,
+             outs=(B.AERIS_DT_F32, B.AERIS_DT_BF16)):
+    bits = synth.make_inputs(kind, seed, shape, 4)
+    q64, k64, v64, do64 = [synth.bf16_bits_to_f64(b) for b in bits]
+    tq, tk, tv, tdo = [to_dev(b) for b in bits]
+    o_ref, lse_ref = orc.winattn_fwd(q64, k64, v64, win, shift, mask, scale)
+    if bwd:
+        dq_ref, dk_ref, dv_ref, _ = orc.winattn_bwd(q64, k64, v64, do64, win, shift, mask, scale)
+    for out in outs:
+        bf = out == B.AERIS_DT_BF16
+        o, lse = B.aeris_winattn_fwd(tq, tk, tv, win, shift, mask, scale, out_dtype=out)
+        torch.cuda.synchronize()
+        check("o", o, o_ref, bf)
+        assert np.abs(to_f64(lse) - lse_ref).max() <= LSE_ABS
+        if bwd:
+            dq, dk, dv = B.aeris_winattn_bwd(tq, tk, tv, o, lse, tdo, win, shift, mask, scale,
+                                             out_dtype=out)
+            torch.cuda.synchronize()
+            check("dq", dq, dq_ref, bf)
+            check("dk", dk, dk_ref, bf)
+            check("dv", dv, dv_ref, bf)
+
+
+# ---- BASELINE config 1: tiny grid, 8x8 windows ------------------------------------------
+@pytest.mark.parametrize("mask", POLICIES)
+@pytest.mark.parametrize("shift", [(0, 0), (4, 4)])
+def test_config1_tiny(mask, shift):
+    run_case((1, 64, 128, 4, 32), (8, 8), shift, mask, seed=1001)
+
+
+# ---- BASELINE config 2: 1-degree-class grid, 12x12 windows, fwd+bwd ---------------------
+@pytest.mark.parametrize("kind", ["normal", "smooth"])
+@pytest.mark.parametrize("shift", [(0, 0), (6, 6)])
+def test_config2_one_degree(kind, shift):
+    run_case((1, 180, 360, 8, 64), (12, 12), shift, B.AERIS_MASK_SWIN, kind=kind, seed=2001,
+             outs=(B.AERIS_DT_F32,) if kind == "smooth" else (B.AERIS_DT_F32, B.AERIS_DT_BF16))
+
+
+def test_config2_smooth_bf16_handover():
+    """Smooth fields give peaked softmax rows, where dS = P o (dP - delta) cancels
+    almost completely.  When the forward output is handed to the backward pass in
+    bf16, delta = sum_c dO*O inherits O's storage rounding (up to one bf16 ulp,
+    2^-8 relative, per element), which does not cancel.  dQ and dK are therefore
+    held to the plain tolerance plus the first-order effect of that perturbation,
+        |d dQ_i| <= scale * e_i * |sum_j P_ij K_j|,  |d dK_j| <= scale * sum_i P_ij e_i |Q_i|,
+        e_i = 2^-8 * sum_c |dO_ic| |O_ic|,
+    evaluated with the oracle's P; O, LSE and dV keep the plain tolerance."""
+    shape, win, shift, mask = (1, 180, 360, 8, 64), (12, 12), (6, 6), B.AERIS_MASK_SWIN
+    Bn, H, W, nh, d = shape
+    scale = 1.0 / np.sqrt(d)
+    bits = synth.make_inputs("smooth", 2001, shape, 4)
+    q64, k64, v64, do64 = [synth.bf16_bits_to_f64(b) for b in bits]
+    tq, tk, tv, tdo = [to_dev(b) for b in bits]
+    o_ref, lse_ref = orc.winattn_fwd(q64, k64, v64, win, shift, mask)
+    dq_ref, dk_ref, dv_ref, _ = orc.winattn_bwd(q64, k64, v64, do64, win, shift, mask)
+    bq, bk = np.zeros_like(q64), np.zeros_like(q64)
+    for wy in range(H // win[0]):
+        for wx in range(W // win[1]):
+            y, x, yh, xh = orc.window_tokens(H, W, win, shift, wy, wx)
+            reg = orc.token_regions(H, W, win, shift, mask, yh, xh)
+            for h in range(nh):
+                bq[0, y, x, h], bk[0, y, x, h] = handover_bounds(
+                    q64[0, y, x, h], k64[0, y, x, h], v64[0, y, x, h], do64[0, y, x, h], reg, scale)
+    o, lse = B.aeris_winattn_fwd(tq, tk, tv, win, shift, mask)
+    dq, dk, dv = B.aeris_winattn_bwd(tq, tk, tv, o, lse, tdo, win, shift, mask)
+    torch.cuda.synchronize()
+    check("o", o, o_ref, True)
+    check("dv", dv, dv_ref, True)
+    assert np.abs(to_f64(lse) - lse_ref).max() <= LSE_ABS
+    check_with_bound("dq", to_f64(dq), dq_ref, bq)
+    check_with_bound("dk", to_f64(dk), dk_ref, bk)
+
+
+# ---- several resident tiles, ragged tails, every head_dim and policy --------------------
+@pytest.mark.parametrize("mask", POLICIES)
+@pytest.mark.parametrize("d", [32, 64, 128])
+def test_ragged_multi_tile(mask, d):
+    # T = 400 = 3*128 + 16 (ragged resident tile), 6*64 + 16 (ragged streamed tile)
+    run_case((1, 40, 60, 2, d), (20, 20), (10, 10), mask, kind="blend", seed=30 + d)
+
+
+@pytest.mark.parametrize("mask", POLICIES)
+def test_six_hour_model_windows(mask):
+    # 30x30 windows, shift 15: T = 900 is not a multiple of 16
+    run_case((1, 60, 90, 2, 128), (30, 30), (15, 15), mask, seed=41)
+
+
+@pytest.mark.parametrize("win,shift", [((1, 1), (0, 0)), ((2, 2), (1, 1)), ((4, 4), (2, 1)),
+                                       ((5, 3), (2, 2)), ((6, 10), (2, 3))])
+def test_small_and_non_square_windows(win, shift):
+    H, W = win[0] * 4, win[1] * 6
+    run_case((2, H, W, 3, 64), win, shift, B.AERIS_MASK_SWIN, seed=51)
+
+
+@pytest.mark.parametrize("shift", [(0, 0), (5, 7)])
+def test_one_window_is_global_attention(shift):
+    run_case((1, 24, 40, 2, 64), (24, 40), shift, B.AERIS_MASK_NONE, seed=61)
+    run_case((1, 24, 40, 2, 64), (24, 40), shift, B.AERIS_MASK_SWIN, seed=62)
+
+
+@pytest.mark.parametrize("shift", [(7, 3), (1, 19)])
+def test_arbitrary_shift(shift):
+    run_case((1, 40, 60, 1, 64), (20, 20), shift, B.AERIS_MASK_SWIN, seed=71)
+
+
+def test_softmax_scale_override_and_peaked_rows():
+    # 1.5 times the default scale at d=64
+    run_case((1, 16, 32, 2, 64), (16, 16), (8, 8), B.AERIS_MASK_LAT, scale=0.18, seed=81)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_paper_window_60x60(d):
+    # two 60x60 windows (T = 3600) of the 24-hour model, seam + corner regions
+    run_case((1, 60, 120, 2, d), (60, 60), (30, 30), B.AERIS_MASK_SWIN, kind="blend", seed=91,
+             outs=(B.AERIS_DT_BF16,))
+
+
+def test_packed_qkv_strides():
+    shape, win, shift, mask = (1, 24, 24, 2, 64), (12, 12), (6, 6), B.AERIS_MASK_SWIN
+    Bn, H, W, nh, d = shape
+    bits = synth.make_inputs("normal", 5, shape, 4)
+    q64, k64, v64, do64 = [synth.bf16_bits_to_f64(b) for b in bits]
+    packed = torch.stack([to_dev(b) for b in bits[:3]], dim=3).contiguous()   # [B,H,W,3,nh,d]
+    dpacked = torch.full_like(packed, float("nan"))
+    tdo = to_dev(bits[3])
+    o = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((Bn, nh, H, W), dtype=torch.float32, device="cuda")
+    p = B.make_params(shape, win, shift, mask, qkv_strides=(3 * nh * d, d))
+    import ctypes
+    lib = B.load()
+    esz = 2
+    ptr = lambda t, i: t.data_ptr() + i * nh * d * esz
+    stream = torch.cuda.current_stream().cuda_stream
+    rc = lib.aeris_winattn_fwd(ctypes.byref(p), ptr(packed, 0), ptr(packed, 1), ptr(packed, 2),
+                               o.data_ptr(), lse.data_ptr(), stream)
+    assert rc == 0
+    ws = torch.empty(B.aeris_winattn_bwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    rc = lib.aeris_winattn_bwd(ctypes.byref(p), ptr(packed, 0), ptr(packed, 1), ptr(packed, 2),
+                               o.data_ptr(), lse.data_ptr(), tdo.data_ptr(), ptr(dpacked, 0),
+                               ptr(dpacked, 1), ptr(dpacked, 2), ws.data_ptr(), ws.numel(), stream)
+    assert rc == 0
+    torch.cuda.synchronize()
+    o_ref, _ = orc.winattn_fwd(q64, k64, v64, win, shift, mask)
+    dq_ref, dk_ref, dv_ref, _ = orc.winattn_bwd(q64, k64, v64, do64, win, shift, mask)
+    check("o", o, o_ref, True)
+    for i, ref in enumerate((dq_ref, dk_ref, dv_ref)):
+        check("d%d" % i, dpacked[:, :, :, i], ref, True)
+
+
+def test_backward_is_bitwise_reproducible_and_staged_equals_whole():
+    shape, win, shift, mask = (1, 40, 60, 2, 128), (20, 20), (10, 10), B.AERIS_MASK_SWIN
+    tq, tk, tv, tdo = [to_dev(b) for b in synth.make_inputs("normal", 9, shape, 4)]
+    o, lse = B.aeris_winattn_fwd(tq, tk, tv, win, shift, mask)
+    a = B.aeris_winattn_bwd(tq, tk, tv, o, lse, tdo, win, shift, mask)
+    b = B.aeris_winattn_bwd(tq, tk, tv, o, lse, tdo, win, shift, mask)
+    ws = torch.empty(B.aeris_winattn_bwd_workspace_bytes(B.make_params(shape, win, shift, mask)),
+                     dtype=torch.uint8, device="cuda")
+    c = [torch.zeros_like(tq) for _ in range(3)]
+    for st in (B.AERIS_BWD_DELTA, B.AERIS_BWD_DKDV, B.AERIS_BWD_DQ):
+        B.aeris_winattn_bwd_stages(tq, tk, tv, o, lse, tdo, win, shift, mask, dq=c[0], dk=c[1],
+                                   dv=c[2], workspace=ws, stages=st)
+    torch.cuda.synchronize()
+    for x, y, z in zip(a, b, c):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+        assert torch.equal(x.view(torch.int16), z.view(torch.int16))
+
+
+def test_errors_raise_on_gpu_box():
+    tq = torch.zeros((1, 16, 16, 1, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.AerisError) as e:
+        B.aeris_winattn_fwd(tq, tq, tq, (5, 4), (0, 0))
+    assert e.value.code == -3
+
+
+# ---- full-size workloads (bench launch configuration): sampled pairs + invariants -------
+def sampled_check(shape, win, shift, mask, kind, seed, bwd, samples, sigmas=None):
+    Bn, H, W, nh, d = shape
+    tensors = synth.make_inputs_device(kind, seed, shape, 4 if bwd else 3, sigmas=sigmas)
+    tq, tk, tv = tensors[:3]
+    o, lse = B.aeris_winattn_fwd(tq, tk, tv, win, shift, mask)
+    if bwd:
+        tdo = tensors[3]
+        dq, dk, dv = B.aeris_winattn_bwd(tq, tk, tv, o, lse, tdo, win, shift, mask)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o.view(-1)[:: 997].float()).all()
+    # whole-grid properties that hold at any size
+    vmin = tv.amin(dim=(1, 2)).float()
+    vmax = tv.amax(dim=(1, 2)).float()
+    assert (o.amax(dim=(1, 2)).float() <= vmax + 1e-2).all()
+    assert (o.amin(dim=(1, 2)).float() >= vmin - 1e-2).all()
+    if bwd:
+        for b in range(Bn):
+            s_dv = dv[b].double().sum(dim=(0, 1))
+            s_do = tdo[b].double().sum(dim=(0, 1))
+            scale_ = dv[b].double().abs().sum(dim=(0, 1))
+            assert ((s_dv - s_do).abs() <= 2e-3 * scale_ + 1e-2).all()
+            qa = (tq[b].double() * dq[b].double()).sum(dim=(0, 1, 3))
+            kb = (tk[b].double() * dk[b].double()).sum(dim=(0, 1, 3))
+            mag = (tq[b].double() * dq[b].double()).abs().sum(dim=(0, 1, 3))
+            assert ((qa - kb).abs() <= 5e-3 * mag + 1e-2).all()
+    for (b, wy, wx, h) in samples:
+        sl = lambda t: to_f64(t[b, :, :, h, :])
+        res = orc.winattn_pair(sl(tq), sl(tk), sl(tv), sl(tdo) if bwd else None, H, W, win,
+                               shift, mask, None, wy, wx)
+        y, x = res["y"], res["x"]
+        check("o", to_f64(o[b, :, :, h, :])[y, x], res["o"], True)
+        assert np.abs(to_f64(lse[b, h])[y, x] - res["lse"]).max() <= LSE_ABS
+        if bwd:
+            # O reaches the backward pass in bf16 here: dQ, dK get the plain tolerance plus
+            # the delta-perturbation bound (see test_config2_smooth_bf16_handover)
+            qw, kw, vw, dow = sl(tq)[y, x], sl(tk)[y, x], sl(tv)[y, x], sl(tdo)[y, x]
+            _, _, yh, xh = orc.window_tokens(H, W, win, shift, wy, wx)
+            reg = orc.token_regions(H, W, win, shift, mask, yh, xh)
+            bq, bk = handover_bounds(qw, kw, vw, dow, reg, 1.0 / np.sqrt(d))
+            check_with_bound("dq", to_f64(dq[b, :, :, h, :])[y, x], res["dq"], bq)
+            check_with_bound("dk", to_f64(dk[b, :, :, h, :])[y, x], res["dk"], bk)
+            check("dv", to_f64(dv[b, :, :, h, :])[y, x], res["dv"], True)
+
+
+def test_config3_quarter_degree_forward_sampled():
+    # interior, lat-seam row, lon-seam column, corner; two heads each
+    samples = [(0, 3, 7, 0), (0, 3, 7, 9), (0, 11, 5, 1), (0, 11, 5, 15), (0, 4, 23, 2),
+               (0, 4, 23, 8), (0, 11, 23, 3), (0, 11, 23, 12)]
+    sampled_check((1, 720, 1440, 16, 64), (60, 60), (30, 30), B.AERIS_MASK_SWIN, "normal", 3001,
+                  False, samples)
+
+
+def test_config4_band_share_fwd_bwd_sampled():
+    samples = [(0, 0, 4, 0), (0, 0, 23, 7), (0, 1, 9, 13), (0, 1, 23, 23)]
+    sampled_check((1, 120, 1440, 24, 128), (60, 60), (30, 30), B.AERIS_MASK_SWIN, "blend", 4001,
+                  True, samples)
+
+
+def test_config5_ensemble_member_fwd_bwd_sampled():
+    # the bench workload's launch shape, two ensemble members (noise levels 0.1 and 2.0)
+    samples = [(0, 5, 5, 1), (0, 11, 23, 6), (1, 11, 2, 9), (1, 7, 23, 15)]
+    sampled_check((2, 720, 1440, 16, 128), (60, 60), (30, 30), B.AERIS_MASK_SWIN, "blend", 5001,
+                  True, samples, sigmas=[0.1, 2.0])
