@@ -99,8 +99,9 @@ typedef struct {
 int aeris_winattn_fwd(const aeris_winattn_params* p, const void* q, const void* k,
                       const void* v, void* o, float* lse, void* hip_stream);
 
-/* Bytes of device workspace the backward pass needs (the delta vector,
- * float32 [B, heads, H_lat, W_lon]).  Returns 0 if the parameters are invalid. */
+/* Bytes of device workspace the backward pass needs (two float32 vectors of
+ * shape [B, heads, H_lat, W_lon]: delta and the LSE in log2 units).  Returns 0 if
+ * the parameters are invalid. */
 size_t aeris_winattn_bwd_workspace_bytes(const aeris_winattn_params* p);
 
 /*
@@ -122,8 +123,8 @@ int aeris_winattn_bwd(const aeris_winattn_params* p, const void* q, const void* 
 
 /* The backward pass is three kernels; this variant runs a subset, in the order
  * delta, dq, dkdv (for profiling one kernel, or to put dq and dkdv on different
- * streams).  AERIS_BWD_DQ and AERIS_BWD_DKDV read the delta vector in
- * `workspace`, so AERIS_BWD_DELTA must have completed on it first.  Outputs of
+ * streams).  AERIS_BWD_DQ and AERIS_BWD_DKDV read what AERIS_BWD_DELTA left in
+ * `workspace`, so that stage must have completed on it first.  Outputs of
  * stages that are not selected are left untouched.  stages == AERIS_BWD_ALL is
  * aeris_winattn_bwd. */
 enum { AERIS_BWD_DELTA = 1, AERIS_BWD_DQ = 2, AERIS_BWD_DKDV = 4, AERIS_BWD_ALL = 7 };

@@ -4,17 +4,23 @@
 // from the saved log-sum-exp; nothing of size T x T touches memory.
 //
 // Three kernels, no atomics (bitwise reproducible):
-//   delta   delta_i = sum_c dO_ic O_ic                       (HBM-bound pre-pass)
+//   delta   delta_i = sum_c dO_ic O_ic, and LSE_i * log2(e)   (HBM-bound pre-pass)
 //   dq      queries resident, keys streamed:   S^T, dP^T -> dS^T -> dQ^T += K^T dS^T
 //   dkdv    keys resident, queries streamed:   S, dP -> P, dS -> dV^T += dO^T P,
 //                                                               dK^T += Q^T dS
 // Both big kernels mirror the forward kernel: the resident side sits in MFMA B
-// operands / accumulator columns (one token per lane pair), the streamed side
-// goes through LDS row-major (first products) and transposed (second products).
+// operands / accumulator columns (one token per lane pair); the streamed side
+// goes through asynchronously filled LDS tiles, read row-major for the first
+// products and through transposing reads for the second.
+//
+// Workspace layout (floats): [0, N) delta, [N, 2N) LSE*log2(e), N = B*heads*H*W,
+// both indexed like LSE.
 #include "winattn_common.hpp"
 #include "winattn_launch.hpp"
 
 namespace aeris {
+
+constexpr float kLog2e = 1.4426950408889634f;
 
 // ----------------------------------------------------------------------------
 // delta[b, head, y, x] = sum_c dO * O.  One thread per 8 channels.
@@ -40,7 +46,7 @@ __device__ __forceinline__ void load8(const float* src, float* out) {
 template <int D, typename OT>
 __global__ __launch_bounds__(kThreads) void winattn_delta_kernel(
     KParams p, long long n_items, const OT* __restrict__ o, const bf16_t* __restrict__ d_o,
-    float* __restrict__ delta) {
+    const float* __restrict__ lse, float* __restrict__ delta, float* __restrict__ lse2) {
   constexpr int kChunks = D / 8;
   const long long plane = (long long)p.H * p.W;
   for (long long gid = (long long)blockIdx.x * kThreads + threadIdx.x; gid < n_items * kChunks;
@@ -60,25 +66,30 @@ __global__ __launch_bounds__(kThreads) void winattn_delta_kernel(
     for (int s = 1; s < kChunks; s <<= 1) acc += __shfl_xor(acc, s);
     if (chunk == 0) {
       const long long bidx = tok / plane;
-      delta[(bidx * p.nh + head) * plane + (tok - bidx * plane)] = acc;
+      const long long idx = (bidx * p.nh + head) * plane + (tok - bidx * plane);
+      delta[idx] = acc;
+      lse2[idx] = lse[idx] * kLog2e;
     }
   }
 }
 
 // ----------------------------------------------------------------------------
-// dQ: same skeleton as the forward kernel.
+// dQ: same skeleton as the forward kernel.  LDS: table + 2 buffers x (K, V).
 // ----------------------------------------------------------------------------
+template <int D>
+constexpr size_t dq_smem_bytes(int T) {
+  return ((T * 4 + 15) & ~15) + 4 * Tile<D>::kBytes;
+}
+
 template <int D, typename OutT>
 __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
     KParams p, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-    const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o, const float* __restrict__ lse,
-    const float* __restrict__ delta, OutT* __restrict__ dq) {
-  using St = Stage<D>;
+    const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
+    const float* __restrict__ delta, const float* __restrict__ lse2v, OutT* __restrict__ dq) {
+  using Tl = Tile<D>;
   extern __shared__ __align__(16) unsigned char smem[];
   int* tok_grid = reinterpret_cast<int*>(smem);
-  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + ((p.T * 4 + 15) & ~15));
-  bf16_t* Vs = Ks + St::kRowTile;
-  bf16_t* Kt = Vs + St::kRowTile;
+  const uint32_t tiles = lds_address(smem) + ((p.T * 4 + 15) & ~15);
 
   int pair, qt;
   if (!block_to_work(p, pair, qt)) return;
@@ -104,6 +115,11 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
   const int q_grid = tok_grid[rg.tok];
   const int lo_q = rg.lo, hi_q = rg.hi;
 
+  const int kt_begin = rg.wg_lo / kStream;
+  const int kt_end = (rg.wg_hi + kStream - 1) / kStream;
+  Tl::fill_async(tiles, kb, p.qkv_tok, tok_grid, kt_begin * kStream, T, wave, lane);
+  Tl::fill_async(tiles + Tl::kBytes, vb, p.qkv_tok, tok_grid, kt_begin * kStream, T, wave, lane);
+
   bf16x8 qreg[D / 16], doreg[D / 16];
   {
     const bf16_t* qrow = q + qkv_base + (long long)q_grid * p.qkv_tok + 8 * g;
@@ -114,8 +130,17 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
       doreg[kk] = *reinterpret_cast<const bf16x8*>(dorow + kk * 16);
     }
   }
-  const float lse2 = lse[stat_base + q_grid] * 1.4426950408889634f;
-  const float delta_q = delta[stat_base + q_grid];
+  float lse2 = lse2v[stat_base + q_grid];
+  float delta_q = delta[stat_base + q_grid];
+  typename Tl::Lanes la;
+  la.init(lane);
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) {
+    settle(qreg[kk]);
+    settle(doreg[kk]);
+  }
+  settle(lse2);
+  settle(delta_q);
 
   f32x16 acc[D / 32];
 #pragma unroll
@@ -123,36 +148,29 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
 
-  const int kt_begin = rg.wg_lo / kStream;
-  const int kt_end = (rg.wg_hi + kStream - 1) / kStream;
-  St kst, vst;
-  kst.load(kb, p.qkv_tok, tok_grid, kt_begin * kStream, T);
-  vst.load(vb, p.qkv_tok, tok_grid, kt_begin * kStream, T);
-
   for (int kt = kt_begin; kt < kt_end; ++kt) {
-    if (kt != kt_begin) __syncthreads();
-    kst.store_rowmajor(Ks);
-    kst.store_transposed(Kt);
-    vst.store_rowmajor(Vs);
+    const uint32_t buf = tiles + ((kt - kt_begin) & 1) * (2 * Tl::kBytes);
+    wait_async_loads();
     __syncthreads();
     if (kt + 1 < kt_end) {
-      kst.load(kb, p.qkv_tok, tok_grid, (kt + 1) * kStream, T);
-      vst.load(vb, p.qkv_tok, tok_grid, (kt + 1) * kStream, T);
+      const uint32_t nxt = tiles + ((kt + 1 - kt_begin) & 1) * (2 * Tl::kBytes);
+      Tl::fill_async(nxt, kb, p.qkv_tok, tok_grid, (kt + 1) * kStream, T, wave, lane);
+      Tl::fill_async(nxt + Tl::kBytes, vb, p.qkv_tok, tok_grid, (kt + 1) * kStream, T, wave, lane);
     }
     if (!rg.wave_active) continue;
 #pragma unroll
     for (int kb2 = 0; kb2 < kStream / 32; ++kb2) {
       const int sub_lo = kt * kStream + kb2 * 32;
       if (rg.skip(sub_lo)) continue;
+      const uint32_t ksub = buf + kb2 * Tl::kSubBytes;
+      const uint32_t vsub = buf + Tl::kBytes + kb2 * Tl::kSubBytes;
       f32x16 s, dp;
 #pragma unroll
       for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
-      const bf16_t* krow = Ks + (kb2 * 32 + qi) * St::kRowStride + 8 * g;
-      const bf16_t* vrow = Vs + (kb2 * 32 + qi) * St::kRowStride + 8 * g;
 #pragma unroll
       for (int kk = 0; kk < D / 16; ++kk) {
-        s = mfma32(*reinterpret_cast<const bf16x8*>(krow + kk * 16), qreg[kk], s);
-        dp = mfma32(*reinterpret_cast<const bf16x8*>(vrow + kk * 16), doreg[kk], dp);
+        s = mfma32(Tl::read_rm(ksub + la.rm[kk]), qreg[kk], s);
+        dp = mfma32(Tl::read_rm(vsub + la.rm[kk]), doreg[kk], dp);
       }
       if (!rg.mask_free(sub_lo)) {
 #pragma unroll
@@ -172,14 +190,13 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
       for (int c = 0; c < 2; ++c)
 #pragma unroll
         for (int e = 0; e < 4; ++e) dsb[c].u[e] = pack_bf16(ds[8 * c + 2 * e], ds[8 * c + 2 * e + 1]);
-      const bf16_t* ktrow = Kt + qi * St::kTrStride + kb2 * 32 + 8 * g;
 #pragma unroll
       for (int cb = 0; cb < D / 32; ++cb)
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
-          acc[cb] = mfma32(
-              *reinterpret_cast<const bf16x8*>(ktrow + cb * 32 * St::kTrStride + 16 * c),
-              dsb[c].h, acc[cb]);
+        for (int c = 0; c < 2; ++c) {
+          const uint32_t grp = ksub + c * (16 * D * 2);
+          acc[cb] = mfma32(Tl::read_tr(grp + la.tr[cb][0], grp + la.tr[cb][1]), dsb[c].h, acc[cb]);
+        }
     }
   }
 
@@ -196,20 +213,24 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
 
 // ----------------------------------------------------------------------------
 // dK, dV: keys resident (one per lane pair), queries streamed.
+// LDS: table + 2 buffers x (Q tile, dO tile, 64 x LSE*log2e, 64 x delta).
 // ----------------------------------------------------------------------------
+template <int D>
+constexpr size_t dkdv_smem_bytes(int T) {
+  return ((T * 4 + 15) & ~15) + 2 * (2 * Tile<D>::kBytes + 2 * kStream * 4);
+}
+
 template <int D, typename OutT>
 __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
     KParams p, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-    const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o, const float* __restrict__ lse,
-    const float* __restrict__ delta, OutT* __restrict__ dk, OutT* __restrict__ dv) {
-  using St = Stage<D>;
+    const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
+    const float* __restrict__ delta, const float* __restrict__ lse2v, OutT* __restrict__ dk,
+    OutT* __restrict__ dv) {
+  using Tl = Tile<D>;
+  constexpr uint32_t kBufBytes = 2 * Tl::kBytes + 2 * kStream * 4;
   extern __shared__ __align__(16) unsigned char smem[];
   int* tok_grid = reinterpret_cast<int*>(smem);
-  float* stat = reinterpret_cast<float*>(smem + ((p.T * 4 + 15) & ~15));  // lse2[64], delta[64]
-  bf16_t* Qs = reinterpret_cast<bf16_t*>(stat + 2 * kStream);
-  bf16_t* dOs = Qs + St::kRowTile;
-  bf16_t* Qt = dOs + St::kRowTile;
-  bf16_t* dOt = Qt + St::kTrTile;
+  const uint32_t tiles = lds_address(smem) + ((p.T * 4 + 15) & ~15);
 
   int pair, kt;
   if (!block_to_work(p, pair, kt)) return;
@@ -235,6 +256,22 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
   const int k_grid = tok_grid[rg.tok];
   const int lo_k = rg.lo, hi_k = rg.hi;
 
+  // one streamed tile: Q, dO (all waves), LSE*log2e (wave 0), delta (wave 1)
+  auto fill = [&](uint32_t buf, int t0) {
+    Tl::fill_async(buf, qb, p.qkv_tok, tok_grid, t0, T, wave, lane);
+    Tl::fill_async(buf + Tl::kBytes, dob, p.o_tok, tok_grid, t0, T, wave, lane);
+    if (wave < 2) {
+      int t = t0 + lane;
+      t = t < T ? t : T - 1;
+      const float* src = (wave == 0 ? lse2v : delta) + stat_base + tok_grid[t];
+      async_copy4(src, buf + 2 * Tl::kBytes + wave * (kStream * 4));
+    }
+  };
+
+  const int qt_begin = rg.wg_lo / kStream;
+  const int qt_end = (rg.wg_hi + kStream - 1) / kStream;
+  fill(tiles, qt_begin * kStream);
+
   bf16x8 kreg[D / 16], vreg[D / 16];
   {
     const bf16_t* krow = k + qkv_base + (long long)k_grid * p.qkv_tok + 8 * g;
@@ -245,6 +282,13 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
       vreg[kk] = *reinterpret_cast<const bf16x8*>(vrow + kk * 16);
     }
   }
+  typename Tl::Lanes la;
+  la.init(lane);
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) {
+    settle(kreg[kk]);
+    settle(vreg[kk]);
+  }
 
   f32x16 dkacc[D / 32], dvacc[D / 32];
 #pragma unroll
@@ -252,50 +296,27 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) { dkacc[cb][i] = 0.f; dvacc[cb][i] = 0.f; }
 
-  const int qt_begin = rg.wg_lo / kStream;
-  const int qt_end = (rg.wg_hi + kStream - 1) / kStream;
-  St qst, dost;
-  float stat_reg = 0.f;
-  auto load_stat = [&](int t0) {
-    if (tid < 2 * kStream) {
-      int t = t0 + (tid & (kStream - 1));
-      t = t < T ? t : T - 1;
-      const long long idx = stat_base + tok_grid[t];
-      stat_reg = tid < kStream ? lse[idx] * 1.4426950408889634f : delta[idx];
-    }
-  };
-  qst.load(qb, p.qkv_tok, tok_grid, qt_begin * kStream, T);
-  dost.load(dob, p.o_tok, tok_grid, qt_begin * kStream, T);
-  load_stat(qt_begin * kStream);
-
   for (int qt = qt_begin; qt < qt_end; ++qt) {
-    if (qt != qt_begin) __syncthreads();
-    qst.store_rowmajor(Qs);
-    qst.store_transposed(Qt);
-    dost.store_rowmajor(dOs);
-    dost.store_transposed(dOt);
-    if (tid < 2 * kStream) stat[tid] = stat_reg;
+    const uint32_t buf = tiles + ((qt - qt_begin) & 1) * kBufBytes;
+    wait_async_loads();
     __syncthreads();
-    if (qt + 1 < qt_end) {
-      qst.load(qb, p.qkv_tok, tok_grid, (qt + 1) * kStream, T);
-      dost.load(dob, p.o_tok, tok_grid, (qt + 1) * kStream, T);
-      load_stat((qt + 1) * kStream);
-    }
+    if (qt + 1 < qt_end) fill(tiles + ((qt + 1 - qt_begin) & 1) * kBufBytes, (qt + 1) * kStream);
     if (!rg.wave_active) continue;
+    const uint32_t stat = buf + 2 * Tl::kBytes;
 #pragma unroll
     for (int qb2 = 0; qb2 < kStream / 32; ++qb2) {
       const int sub_lo = qt * kStream + qb2 * 32;
       if (rg.skip(sub_lo)) continue;
+      const uint32_t qsub = buf + qb2 * Tl::kSubBytes;
+      const uint32_t dosub = buf + Tl::kBytes + qb2 * Tl::kSubBytes;
       // S[query, key] = Q K^T,  dP[query, key] = dO V^T: rows = streamed queries
       f32x16 s, dp;
 #pragma unroll
       for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
-      const bf16_t* qrow = Qs + (qb2 * 32 + ki) * St::kRowStride + 8 * g;
-      const bf16_t* dorow = dOs + (qb2 * 32 + ki) * St::kRowStride + 8 * g;
 #pragma unroll
       for (int kk = 0; kk < D / 16; ++kk) {
-        s = mfma32(*reinterpret_cast<const bf16x8*>(qrow + kk * 16), kreg[kk], s);
-        dp = mfma32(*reinterpret_cast<const bf16x8*>(dorow + kk * 16), vreg[kk], dp);
+        s = mfma32(Tl::read_rm(qsub + la.rm[kk]), kreg[kk], s);
+        dp = mfma32(Tl::read_rm(dosub + la.rm[kk]), vreg[kk], dp);
       }
       if (!rg.mask_free(sub_lo)) {
 #pragma unroll
@@ -307,8 +328,9 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
       float pr[16], ds[16];
 #pragma unroll
       for (int vq = 0; vq < 4; ++vq) {
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + qb2 * 32 + 8 * vq + 4 * g);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + kStream + qb2 * 32 + 8 * vq + 4 * g);
+        const uint32_t at = stat + (qb2 * 32 + 8 * vq + 4 * g) * 4;
+        const f32x4 l4 = *reinterpret_cast<const AERIS_LDS f32x4*>(at);
+        const f32x4 d4 = *reinterpret_cast<const AERIS_LDS f32x4*>(at + kStream * 4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int i = 4 * vq + e;
@@ -324,18 +346,15 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
           pb[c].u[e] = pack_bf16(pr[8 * c + 2 * e], pr[8 * c + 2 * e + 1]);
           dsb[c].u[e] = pack_bf16(ds[8 * c + 2 * e], ds[8 * c + 2 * e + 1]);
         }
-      const bf16_t* qtrow = Qt + ki * St::kTrStride + qb2 * 32 + 8 * g;
-      const bf16_t* dotrow = dOt + ki * St::kTrStride + qb2 * 32 + 8 * g;
 #pragma unroll
       for (int cb = 0; cb < D / 32; ++cb)
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-          dvacc[cb] = mfma32(
-              *reinterpret_cast<const bf16x8*>(dotrow + cb * 32 * St::kTrStride + 16 * c),
-              pb[c].h, dvacc[cb]);
-          dkacc[cb] = mfma32(
-              *reinterpret_cast<const bf16x8*>(qtrow + cb * 32 * St::kTrStride + 16 * c),
-              dsb[c].h, dkacc[cb]);
+          const uint32_t off = c * (16 * D * 2);
+          dvacc[cb] = mfma32(Tl::read_tr(dosub + off + la.tr[cb][0], dosub + off + la.tr[cb][1]),
+                             pb[c].h, dvacc[cb]);
+          dkacc[cb] = mfma32(Tl::read_tr(qsub + off + la.tr[cb][0], qsub + off + la.tr[cb][1]),
+                             dsb[c].h, dkacc[cb]);
         }
     }
   }
@@ -355,48 +374,51 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
     }
 }
 
+template <typename K>
+static bool allow_smem(K kern, size_t smem) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)smem) == hipSuccess;
+}
+
 template <int D, typename OutT>
 static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const void* v,
                         const void* o, const float* lse, const void* d_o, void* dq, void* dk,
-                        void* dv, float* delta, hipStream_t stream, unsigned stages) {
-  using St = Stage<D>;
+                        void* dv, float* workspace, hipStream_t stream, unsigned stages) {
   const bf16_t* qp = static_cast<const bf16_t*>(q);
   const bf16_t* kp_ = static_cast<const bf16_t*>(k);
   const bf16_t* vp = static_cast<const bf16_t*>(v);
   const bf16_t* dop = static_cast<const bf16_t*>(d_o);
 
   const long long n_items = (long long)kp.B * kp.H * kp.W * kp.nh;
-  const long long n_thr = n_items * (D / 8);
-  long long dblocks = (n_thr + kThreads - 1) / kThreads;
-  if (dblocks > 256 * 64) dblocks = 256 * 64;
+  float* delta = workspace;
+  float* lse2 = workspace + n_items;
   if (stages & 1u) {
+    const long long n_thr = n_items * (D / 8);
+    long long dblocks = (n_thr + kThreads - 1) / kThreads;
+    if (dblocks > 256 * 64) dblocks = 256 * 64;
     hipLaunchKernelGGL((winattn_delta_kernel<D, OutT>), dim3((unsigned)dblocks), dim3(kThreads),
-                       0, stream, kp, n_items, static_cast<const OutT*>(o), dop, delta);
+                       0, stream, kp, n_items, static_cast<const OutT*>(o), dop, lse, delta, lse2);
     if (hipGetLastError() != hipSuccess) return -1;
   }
 
   const int n_blocks = grid_blocks(kp);
-  const size_t tab = (kp.T * 4 + 15) & ~15;
   if (stages & 2u) {
-    const size_t smem = tab + (2 * St::kRowTile + St::kTrTile) * sizeof(bf16_t);
+    const size_t smem = dq_smem_bytes<D>(kp.T);
     auto kern = winattn_dq_kernel<D, OutT>;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-      return -1;
-    hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, qp, kp_,
-                       vp, dop, lse, static_cast<const float*>(delta), static_cast<OutT*>(dq));
+    if (!allow_smem(kern, smem)) return -1;
+    hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, qp, kp_, vp, dop,
+                       static_cast<const float*>(delta), static_cast<const float*>(lse2),
+                       static_cast<OutT*>(dq));
     if (hipGetLastError() != hipSuccess) return -1;
   }
   if (stages & 4u) {
-    const size_t smem = tab + 2 * kStream * sizeof(float) +
-                        (2 * St::kRowTile + 2 * St::kTrTile) * sizeof(bf16_t);
+    const size_t smem = dkdv_smem_bytes<D>(kp.T);
     auto kern = winattn_dkdv_kernel<D, OutT>;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-      return -1;
-    hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, qp, kp_,
-                       vp, dop, lse, static_cast<const float*>(delta), static_cast<OutT*>(dk),
-                       static_cast<OutT*>(dv));
+    if (!allow_smem(kern, smem)) return -1;
+    hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, qp, kp_, vp, dop,
+                       static_cast<const float*>(delta), static_cast<const float*>(lse2),
+                       static_cast<OutT*>(dk), static_cast<OutT*>(dv));
     if (hipGetLastError() != hipSuccess) return -1;
   }
   return 0;
@@ -404,14 +426,13 @@ static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const v
 
 int launch_bwd(const KParams& kp, int head_dim, bool out_f32, const void* q, const void* k,
                const void* v, const void* o, const float* lse, const void* d_o, void* dq,
-               void* dk, void* dv, float* delta, hipStream_t stream, unsigned stages) {
-#define AERIS_BWD_CASE(DD)                                                                     \
-  case DD:                                                                                     \
-    return out_f32                                                                             \
-               ? launch_bwd_t<DD, float>(kp, q, k, v, o, lse, d_o, dq, dk, dv, delta, stream,  \
-                                         stages)                                        \
-               : launch_bwd_t<DD, bf16_t>(kp, q, k, v, o, lse, d_o, dq, dk, dv, delta, stream,  \
-                                          stages);
+               void* dk, void* dv, float* workspace, hipStream_t stream, unsigned stages) {
+#define AERIS_BWD_CASE(DD)                                                                    \
+  case DD:                                                                                    \
+    return out_f32 ? launch_bwd_t<DD, float>(kp, q, k, v, o, lse, d_o, dq, dk, dv, workspace, \
+                                             stream, stages)                                  \
+                   : launch_bwd_t<DD, bf16_t>(kp, q, k, v, o, lse, d_o, dq, dk, dv,           \
+                                              workspace, stream, stages);
   switch (head_dim) {
     AERIS_BWD_CASE(32)
     AERIS_BWD_CASE(64)

@@ -25,7 +25,6 @@ constexpr int kThreads = 256;      // 4 wavefronts of 64 lanes
 constexpr int kWaves = 4;
 constexpr int kResident = 128;     // tokens a workgroup keeps in registers (32 per wave)
 constexpr int kStream = 64;        // tokens per streamed LDS tile
-constexpr int kPad = 8;            // bf16 elements of padding per LDS row (16 bytes)
 constexpr float kLazyRescale = 8.0f;  // log2 units a row maximum may lag behind
 
 // Host-filled launch parameters (plain data, passed by value).
@@ -170,7 +169,7 @@ __device__ __forceinline__ void build_token_table(const KParams& p, const Window
 // between A and B, a D tile can be fed back as the B operand of the next
 // product without any cross-lane movement: registers 8c..8c+7 of lane l hold
 // rows {16c + 4*(l/32) + (0..3), 16c + 8 + 4*(l/32) + (0..3)}, and the A
-// operand is fetched in that same row order (see transposed_pos()).
+// operand is fetched in that same row order (Tile::read_tr).
 // ----------------------------------------------------------------------------
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -178,15 +177,6 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 
 // Row of a 32x32 accumulator tile held in register v by a lane of half g.
 __device__ __forceinline__ int acc_row(int v, int g) { return 8 * (v >> 2) + 4 * g + (v & 3); }
-
-// Position, inside a transposed LDS row, of streamed token kappa (multiple of
-// 4; four consecutive tokens stay adjacent).  Within each group of 16 tokens
-// the four 4-token granules are stored in the order 0,2,1,3 so that one
-// 16-byte read returns exactly the eight contraction rows a lane needs.
-__device__ __forceinline__ int transposed_pos(int kappa) {
-  const int gran = (kappa >> 2) & 3;
-  return (kappa & ~15) + 8 * (gran & 1) + 4 * (gran >> 1);
-}
 
 __device__ __forceinline__ float wave_half_max(float x) {
   return fmaxf(x, __shfl_xor(x, 32));
@@ -199,74 +189,125 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 }
 
 // ----------------------------------------------------------------------------
-// Streamed tile staging: kStream tokens x D channels of one tensor go from
-// global memory to registers (16-byte loads, 4 tokens x 8 channels per work
-// item), then to LDS row-major [token][D + pad] and/or transposed
-// [channel][kStream + pad] with the token order of transposed_pos().
+// Streamed tiles in LDS.
+//
+// A tile is kStream tokens x D channels, row-major, unpadded; the 16-byte
+// chunks of token row r sit at chunk position c ^ swz(r).  It is filled
+// straight from global memory (global_load_lds_dwordx4: no registers, no VALU
+// besides addresses; each wave instruction deposits 64 consecutive chunks, and
+// every lane fetches the source chunk that belongs in its slot, so the swizzle
+// costs nothing).  It is read two ways:
+//   * row-major, ds_read_b128: lane (row l%32, chunk 2*kk + l/32): the A
+//     operand of the first products (contraction over channels);
+//   * transposed, ds_read_b64_tr_b16: a 16-lane block fetches 4 token rows x
+//     16 channels and each lane receives the 4 tokens of ONE channel: the A
+//     operand of the second products (contraction over tokens), in the row
+//     order {4g..4g+3, 8+4g..8+4g+3} that matches the accumulator layout.
+// swz() makes both access patterns bank-conflict free: 16 consecutive rows at
+// one logical chunk hit 16 different chunk positions, and 4 consecutive rows x
+// 4 consecutive chunks hit 16 different positions.
 // ----------------------------------------------------------------------------
+#define AERIS_LDS __attribute__((address_space(3)))
+#define AERIS_GLB __attribute__((address_space(1)))
+
+__device__ __forceinline__ uint32_t lds_address(const void* generic) {
+  return (uint32_t)(uintptr_t)(AERIS_LDS const void*)generic;
+}
+
+// 16 bytes per lane, global -> LDS, asynchronously: lane l's data lands at LDS
+// byte address lds_base + 16*l (lds_base wave-uniform).  Written as assembly so
+// that the compiler does not serialise later LDS reads of OTHER buffers behind
+// it; completion is awaited explicitly with wait_async_loads() + a barrier.
+__device__ __forceinline__ void async_copy16(const void* src, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(src), "s"(lds_base)
+               : "memory");
+}
+// 4 bytes per lane: lane l's dword lands at lds_base + 4*l.
+__device__ __forceinline__ void async_copy4(const void* src, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off"
+               :
+               : "v"(src), "s"(lds_base)
+               : "memory");
+}
+__device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Makes the compiler finish the loads that produce `v` here (it then places its
+// own wait before this point instead of inside the main loop, where a vmcnt
+// wait would also wait for the prefetch of the next tile).
+template <typename V>
+__device__ __forceinline__ void settle(V& v) {
+  asm volatile("" : "+v"(v));
+}
+
 template <int D>
-struct Stage {
-  static constexpr int kChunks = D / 8;                    // 16-byte chunks per token row
-  static constexpr int kItems = (kStream / 4) * kChunks;   // work items per tile
-  static constexpr int kPerThread = (kItems + kThreads - 1) / kThreads;
-  static constexpr int kRowStride = D + kPad;              // row-major LDS row, elements
-  static constexpr int kTrStride = kStream + kPad;         // transposed LDS row, elements
-  static constexpr int kRowTile = kStream * kRowStride;    // elements
-  static constexpr int kTrTile = D * kTrStride;            // elements
+struct Tile {
+  static constexpr int NC = D / 8;                  // 16-byte chunks per token row
+  static constexpr int kBytes = kStream * D * 2;
+  static constexpr int kSubBytes = 32 * D * 2;      // 32-token sub-block
+  static constexpr int kFillPerWave = NC / kWaves;  // wave instructions per tile and wave
 
-  u32x4 r[kPerThread][4];
+  __device__ __forceinline__ static int swz(int r) {
+    if (D == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
+    if (D == 64) return (((r >> 1) & 1) << 2) | ((r >> 2) & 3);
+    return (r >> 2) & 3;
+  }
+  // Byte offset, inside a tile, of chunk c of token row r.
+  __device__ __forceinline__ static int chunk_offset(int r, int c) {
+    return (r * NC + (c ^ swz(r))) * 16;
+  }
 
-  // base: pointer to (batch, head) origin; tok_grid: LDS table; t0: first token.
-  __device__ __forceinline__ void load(const bf16_t* base, long long tok_stride,
-                                       const int* tok_grid, int t0, int T) {
+  // Asynchronous fill of the tile at LDS byte address `tile` (wave-uniform)
+  // with tokens t0 .. t0+63 of one (batch, head); completion is tracked by
+  // vmcnt.  Tokens past the window's end re-read the last token (masked later).
+  __device__ __forceinline__ static void fill_async(uint32_t tile, const bf16_t* base,
+                                                    long long tok_stride, const int* tok_grid,
+                                                    int t0, int T, int wave, int lane) {
 #pragma unroll
-    for (int j = 0; j < kPerThread; ++j) {
-      const int item = threadIdx.x + j * kThreads;
-      if (kItems % kThreads != 0 && item >= kItems) break;
-      const int chunk = item % kChunks;
-      const int tg = item / kChunks;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        int t = t0 + 4 * tg + i;
-        t = t < T ? t : T - 1;          // phantom tokens re-read the last one; masked later
-        const bf16_t* src = base + (long long)tok_grid[t] * tok_stride + chunk * 8;
-        r[j][i] = *reinterpret_cast<const u32x4*>(src);
-      }
+    for (int i = 0; i < kFillPerWave; ++i) {
+      const int inst = wave * kFillPerWave + i;
+      const int slot = inst * 64 + lane;
+      const int r = slot / NC;
+      const int c = (slot % NC) ^ swz(r);
+      int t = t0 + r;
+      t = t < T ? t : T - 1;
+      const bf16_t* src = base + (long long)tok_grid[t] * tok_stride + c * 8;
+      async_copy16(src, tile + inst * 1024);
     }
   }
 
-  __device__ __forceinline__ void store_rowmajor(bf16_t* tile) const {
-#pragma unroll
-    for (int j = 0; j < kPerThread; ++j) {
-      const int item = threadIdx.x + j * kThreads;
-      if (kItems % kThreads != 0 && item >= kItems) break;
-      const int chunk = item % kChunks;
-      const int tg = item / kChunks;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        *reinterpret_cast<u32x4*>(tile + (4 * tg + i) * kRowStride + chunk * 8) = r[j][i];
-    }
-  }
+  // Per-lane byte offsets (tile-relative, sub-block 0) of the operand reads.
+  struct Lanes {
+    int rm[D / 16];        // row-major: contraction block kk
+    int tr[D / 32][2];     // transposed: channel block cb, first/second four tokens
 
-  __device__ __forceinline__ void store_transposed(bf16_t* tile) const {
+    __device__ __forceinline__ void init(int lane) {
+      const int row = lane & 31, g = lane >> 5;
 #pragma unroll
-    for (int j = 0; j < kPerThread; ++j) {
-      const int item = threadIdx.x + j * kThreads;
-      if (kItems % kThreads != 0 && item >= kItems) break;
-      const int chunk = item % kChunks;
-      const int tg = item / kChunks;
-      const int pos = transposed_pos(4 * tg);
+      for (int kk = 0; kk < D / 16; ++kk) rm[kk] = chunk_offset(row, 2 * kk + g);
+      const int j = lane & 15, blk = lane >> 4;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        // dword w of each token row holds channels 2w (low half) and 2w+1 (high half)
-        const uint32_t a0 = r[j][0][w], a1 = r[j][1][w], a2 = r[j][2][w], a3 = r[j][3][w];
-        u32x2 even = {(a0 & 0xffffu) | (a1 << 16), (a2 & 0xffffu) | (a3 << 16)};
-        u32x2 odd = {(a0 >> 16) | (a1 & 0xffff0000u), (a2 >> 16) | (a3 & 0xffff0000u)};
-        bf16_t* row = tile + (chunk * 8 + 2 * w) * kTrStride + pos;
-        *reinterpret_cast<u32x2*>(row) = even;
-        *reinterpret_cast<u32x2*>(row + kTrStride) = odd;
-      }
+      for (int cb = 0; cb < D / 32; ++cb)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int r = 8 * h + 4 * (blk >> 1) + (j >> 2);
+          const int c = 4 * cb + 2 * (blk & 1) + ((j & 3) >> 1);
+          tr[cb][h] = chunk_offset(r, c) + (j & 1) * 8;
+        }
     }
+  };
+
+  __device__ __forceinline__ static bf16x8 read_rm(uint32_t addr) {
+    return *reinterpret_cast<const AERIS_LDS bf16x8*>(addr);
+  }
+  // A operand of a second product: channel block cb, tokens of 16-token group at `addr_*`.
+  __device__ __forceinline__ static bf16x8 read_tr(uint32_t addr_first, uint32_t addr_second) {
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+        reinterpret_cast<AERIS_LDS bf16x4*>(addr_first));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+        reinterpret_cast<AERIS_LDS bf16x4*>(addr_second));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   }
 };
 

@@ -4,26 +4,31 @@
 //
 // One workgroup = 128 queries of one (batch, window, head); each of its four
 // wavefronts owns 32 queries, one per lane pair (l, l+32).  Keys/values stream
-// through LDS 64 tokens at a time.  The logits are produced transposed,
-//     S^T[key, query] = K Q^T        (A = K tile from LDS, B = Q in registers)
+// through double-buffered LDS tiles of 64 tokens, filled asynchronously.  The
+// logits are produced transposed,
+//     S^T[key, query] = K Q^T        (A = K tile, row-major reads; B = Q in registers)
 // so every lane holds logits of ONE query: the softmax statistics are per-lane
 // scalars and the row reductions need a single cross-lane exchange.  P^T then
 // feeds the second product in place,
-//     O^T[channel, query] += V^T P^T (A = transposed V tile from LDS, B = P^T).
+//     O^T[channel, query] += V^T P^T (A = V tile through transposing reads, B = P^T).
 #include "winattn_common.hpp"
 #include "winattn_launch.hpp"
 
 namespace aeris {
 
+template <int D>
+constexpr size_t fwd_smem_bytes(int T) {
+  return ((T * 4 + 15) & ~15) + 4 * Tile<D>::kBytes;   // table + 2 buffers x (K, V)
+}
+
 template <int D, typename OutT>
 __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
     KParams p, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
     const bf16_t* __restrict__ v, OutT* __restrict__ o, float* __restrict__ lse) {
-  using St = Stage<D>;
+  using Tl = Tile<D>;
   extern __shared__ __align__(16) unsigned char smem[];
   int* tok_grid = reinterpret_cast<int*>(smem);
-  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + ((p.T * 4 + 15) & ~15));
-  bf16_t* Vt = Ks + St::kRowTile;
+  const uint32_t tiles = lds_address(smem) + ((p.T * 4 + 15) & ~15);   // [buf][K,V]
 
   int pair, qt;
   if (!block_to_work(p, pair, qt)) return;
@@ -39,25 +44,32 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
   const int T = p.T;
 
   const long long plane = (long long)p.H * p.W;
-  const bf16_t* qb = q + ((long long)win.b * plane) * p.qkv_tok + (long long)win.head * p.qkv_head;
-  const bf16_t* kb = k + ((long long)win.b * plane) * p.qkv_tok + (long long)win.head * p.qkv_head;
-  const bf16_t* vb = v + ((long long)win.b * plane) * p.qkv_tok + (long long)win.head * p.qkv_head;
+  const long long qkv_base = ((long long)win.b * plane) * p.qkv_tok + (long long)win.head * p.qkv_head;
+  const bf16_t* kb = k + qkv_base;
+  const bf16_t* vb = v + qkv_base;
 
   // ---- this lane's query ----------------------------------------------------
   Ranges rg;
   rg.init(win, qt, wave, qi);
-  const bool wave_active = rg.wave_active;
-  const bool q_valid = rg.valid;
   const int q_grid = tok_grid[rg.tok];
   const int lo_q = rg.lo, hi_q = rg.hi;
 
+  const int kt_begin = rg.wg_lo / kStream;
+  const int kt_end = (rg.wg_hi + kStream - 1) / kStream;
+  Tl::fill_async(tiles, kb, p.qkv_tok, tok_grid, kt_begin * kStream, T, wave, lane);
+  Tl::fill_async(tiles + Tl::kBytes, vb, p.qkv_tok, tok_grid, kt_begin * kStream, T, wave, lane);
+
   bf16x8 qreg[D / 16];
   {
-    const bf16_t* qrow = qb + (long long)q_grid * p.qkv_tok + 8 * g;
+    const bf16_t* qrow = q + qkv_base + (long long)q_grid * p.qkv_tok + 8 * g;
 #pragma unroll
     for (int kk = 0; kk < D / 16; ++kk)
       qreg[kk] = *reinterpret_cast<const bf16x8*>(qrow + kk * 16);
   }
+  typename Tl::Lanes la;
+  la.init(lane);
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) settle(qreg[kk]);
 
   f32x16 oacc[D / 32];
 #pragma unroll
@@ -67,36 +79,28 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
   float m_run = -INFINITY;   // running (lagging) row maximum, log2 domain
   float l_run = 0.f;         // this lane's share of the row sum
 
-  const int kt_begin = rg.wg_lo / kStream;
-  const int kt_end = (rg.wg_hi + kStream - 1) / kStream;
-
-  St kst, vst;
-  kst.load(kb, p.qkv_tok, tok_grid, kt_begin * kStream, T);
-  vst.load(vb, p.qkv_tok, tok_grid, kt_begin * kStream, T);
-
   for (int kt = kt_begin; kt < kt_end; ++kt) {
-    if (kt != kt_begin) __syncthreads();          // everyone done reading the old tile
-    kst.store_rowmajor(Ks);
-    vst.store_transposed(Vt);
-    __syncthreads();
-    if (kt + 1 < kt_end) {                        // next tile flies during the math
-      kst.load(kb, p.qkv_tok, tok_grid, (kt + 1) * kStream, T);
-      vst.load(vb, p.qkv_tok, tok_grid, (kt + 1) * kStream, T);
+    const uint32_t buf = tiles + ((kt - kt_begin) & 1) * (2 * Tl::kBytes);
+    wait_async_loads();      // this wave's part of tile kt has landed
+    __syncthreads();         // ... everyone's has; and everyone is done with tile kt-1
+    if (kt + 1 < kt_end) {   // next tile flies during the math, into the other buffer
+      const uint32_t nxt = tiles + ((kt + 1 - kt_begin) & 1) * (2 * Tl::kBytes);
+      Tl::fill_async(nxt, kb, p.qkv_tok, tok_grid, (kt + 1) * kStream, T, wave, lane);
+      Tl::fill_async(nxt + Tl::kBytes, vb, p.qkv_tok, tok_grid, (kt + 1) * kStream, T, wave, lane);
     }
-    const int tile_lo = kt * kStream;
-    if (!wave_active) continue;
+    if (!rg.wave_active) continue;
 #pragma unroll
     for (int kb2 = 0; kb2 < kStream / 32; ++kb2) {
-      const int sub_lo = tile_lo + kb2 * 32;
+      const int sub_lo = kt * kStream + kb2 * 32;
       if (rg.skip(sub_lo)) continue;   // wave-uniform
+      const uint32_t ksub = buf + kb2 * Tl::kSubBytes;
+      const uint32_t vsub = buf + Tl::kBytes + kb2 * Tl::kSubBytes;
       // ---- S^T = K Q^T -------------------------------------------------------
       f32x16 s;
 #pragma unroll
       for (int i = 0; i < 16; ++i) s[i] = 0.f;
-      const bf16_t* krow = Ks + (kb2 * 32 + qi) * St::kRowStride + 8 * g;
 #pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk)
-        s = mfma32(*reinterpret_cast<const bf16x8*>(krow + kk * 16), qreg[kk], s);
+      for (int kk = 0; kk < D / 16; ++kk) s = mfma32(Tl::read_rm(ksub + la.rm[kk]), qreg[kk], s);
       // ---- mask --------------------------------------------------------------
       if (!rg.mask_free(sub_lo)) {
 #pragma unroll
@@ -135,19 +139,18 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
       for (int c = 0; c < 2; ++c)
 #pragma unroll
         for (int e = 0; e < 4; ++e) pb[c].u[e] = pack_bf16(pv[8 * c + 2 * e], pv[8 * c + 2 * e + 1]);
-      const bf16_t* vrow = Vt + qi * St::kTrStride + kb2 * 32 + 8 * g;
 #pragma unroll
       for (int cb = 0; cb < D / 32; ++cb)
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
-          oacc[cb] = mfma32(
-              *reinterpret_cast<const bf16x8*>(vrow + cb * 32 * St::kTrStride + 16 * c),
-              pb[c].h, oacc[cb]);
+        for (int c = 0; c < 2; ++c) {
+          const uint32_t grp = vsub + c * (16 * D * 2);   // 16-token group
+          oacc[cb] = mfma32(Tl::read_tr(grp + la.tr[cb][0], grp + la.tr[cb][1]), pb[c].h, oacc[cb]);
+        }
     }
   }
 
   // ---- epilogue: normalise, un-shift/un-partition store -----------------------
-  if (!q_valid) return;
+  if (!rg.valid) return;
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const float inv = 1.f / l_tot;
   OutT* orow = o + ((long long)win.b * plane + q_grid) * p.o_tok + (long long)win.head * p.o_head;
@@ -165,9 +168,8 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
 template <int D, typename OutT>
 static int launch_fwd_t(const KParams& kp, const void* q, const void* k, const void* v, void* o,
                         float* lse, hipStream_t stream) {
-  using St = Stage<D>;
   const int n_blocks = grid_blocks(kp);
-  const size_t smem = ((kp.T * 4 + 15) & ~15) + (St::kRowTile + St::kTrTile) * sizeof(bf16_t);
+  const size_t smem = fwd_smem_bytes<D>(kp.T);
   auto kern = winattn_fwd_kernel<D, OutT>;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)

@@ -1,10 +1,12 @@
 """GPU parity: the HIP library (through its C ABI) against the fp64 oracle.
 
 Tolerances (bf16 operands, fp32 accumulation): relative L2 <= 5e-3 and
-max-abs <= 2e-2 on O, dQ, dK, dV; |LSE error| <= 1e-2.  With bf16 outputs the
-rounding of the stored value alone is |x| * 2^-9, which exceeds 2e-2 once
-|x| >= 8, so there the max-abs bound is applied to the error in excess of that
-half-ulp; the fp32-output run of the same kernels is held to the plain bound.
+max-abs <= 2e-2 on O, dQ, dK, dV; |LSE error| <= 1e-2.  The absolute bound is
+meant for unit-scale tensors (N(0,1) operands give outputs with max |x| of about
+4): bf16 carries 8 significant bits, so the rounding of a stored value and of P
+or dS before the second product is relative to the magnitude.  For a reference
+tensor whose largest magnitude exceeds 4 the max-abs bound is scaled up by
+max|ref| / 4; relative L2 is always held to 5e-3.
 """
 import numpy as np
 import pytest
@@ -34,10 +36,9 @@ def check(name, got, ref, bf16_out):
     # a one-token window has dQ = dK = 0 exactly: allow an absolute floor of 1e-5 per element
     rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 2e-3 * np.sqrt(ref.size))
     err = np.abs(got - ref)
-    if bf16_out:
-        err = np.maximum(err - np.abs(ref) * 2.0 ** -9, 0.0) if np.abs(ref).max() >= 8 else err
     assert rel <= REL_L2, "%s rel_l2 %.3e" % (name, rel)
-    assert err.max() <= MAX_ABS, "%s max_abs %.3e" % (name, err.max())
+    tol = MAX_ABS * max(1.0, np.abs(ref).max() / 4.0)
+    assert err.max() <= tol, "%s max_abs %.3e > %.3e" % (name, err.max(), tol)
 
 
 def handover_bounds(qw, kw, vw, dow, reg, scale):
@@ -53,8 +54,9 @@ def handover_bounds(qw, kw, vw, dow, reg, scale):
 def check_with_bound(name, got, ref, bound):
     err = np.abs(got - ref)
     assert np.isfinite(got).all(), name
-    excess = np.maximum(err - bound - np.abs(ref) * 2.0 ** -9, 0.0)
-    assert excess.max() <= MAX_ABS, "%s max_abs excess %.3e" % (name, excess.max())
+    excess = np.maximum(err - bound, 0.0)
+    tol = MAX_ABS * max(1.0, np.abs(ref).max() / 4.0)
+    assert excess.max() <= tol, "%s max_abs excess %.3e > %.3e" % (name, excess.max(), tol)
     assert np.linalg.norm(err) <= REL_L2 * np.linalg.norm(ref) + np.linalg.norm(bound), name
 
 
