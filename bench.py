@@ -61,6 +61,9 @@ def main():
     ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-pairs", type=int, default=8)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="end with three 1 GiB read + 1 GiB write elementwise kernels "
+                         "(the last three dispatches), to scale rocprofv3 FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (pairs of (batch, window, head) are "
@@ -157,6 +160,14 @@ def main():
                       "layers_per_step": len(wl["layers"]),
                       "model_tflop_per_step": round(model_flops / 1e12, 2)},
            "kernels": kern, "roofline": roofline}
+
+    if args.calibrate_copy:
+        a = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            torch.add(a, 1.0, out=b)
+        torch.cuda.synchronize()
+        del a, b
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, tq, tk, tv, tdo, args.cpu_pairs)

@@ -99,9 +99,9 @@ typedef struct {
 int aeris_winattn_fwd(const aeris_winattn_params* p, const void* q, const void* k,
                       const void* v, void* o, float* lse, void* hip_stream);
 
-/* Bytes of device workspace the backward pass needs (two float32 vectors of
- * shape [B, heads, H_lat, W_lon]: delta and the LSE in log2 units).  Returns 0 if
- * the parameters are invalid. */
+/* Bytes of device workspace the backward pass needs (two float32 vectors with one
+ * entry per token and head, plus padding: delta and the LSE in log2 units, in
+ * the kernels' window order).  Returns 0 if the parameters are invalid. */
 size_t aeris_winattn_bwd_workspace_bytes(const aeris_winattn_params* p);
 
 /*

@@ -98,7 +98,7 @@ int aeris_winattn_fwd(const aeris_winattn_params* p, const void* q, const void* 
 size_t aeris_winattn_bwd_workspace_bytes(const aeris_winattn_params* p) {
   Strides s;
   if (resolve(p, &s) != AERIS_OK) return 0;
-  return 2 * (size_t)p->B * p->heads * p->H_lat * p->W_lon * sizeof(float);
+  return aeris::bwd_workspace_bytes(derive(p, s));
 }
 
 int aeris_winattn_bwd(const aeris_winattn_params* p, const void* q, const void* k, const void* v,

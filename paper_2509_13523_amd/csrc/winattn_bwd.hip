@@ -13,17 +13,22 @@
 // goes through asynchronously filled LDS tiles, read row-major for the first
 // products and through transposing reads for the second.
 //
-// Workspace layout (floats): [0, N) delta, [N, 2N) LSE*log2(e), N = B*heads*H*W,
-// both indexed like LSE.
+// Workspace (floats): two vectors of n_pairs * T + 64 entries, delta first, then
+// LSE * log2(e); both in WINDOW order -- entry pair * T + t belongs to token t of
+// that (batch, window, head) in the kernels' token enumeration -- so the
+// statistics of a streamed tile are 64 consecutive floats.
 #include "winattn_common.hpp"
 #include "winattn_launch.hpp"
 
 namespace aeris {
 
-constexpr float kLog2e = 1.4426950408889634f;
+__host__ __device__ inline long long stat_entries(const KParams& p) {
+  return (long long)p.n_pairs * p.T + kStream;
+}
 
 // ----------------------------------------------------------------------------
-// delta[b, head, y, x] = sum_c dO * O.  One thread per 8 channels.
+// delta and LSE*log2e in window order.  One thread per 8 channels of one token
+// of one (batch, window, head); the D/8 threads of a token reduce by shuffles.
 // ----------------------------------------------------------------------------
 __device__ __forceinline__ void load8(const bf16_t* src, float* out) {
   const u32x4 r = *reinterpret_cast<const u32x4*>(src);
@@ -45,31 +50,33 @@ __device__ __forceinline__ void load8(const float* src, float* out) {
 
 template <int D, typename OT>
 __global__ __launch_bounds__(kThreads) void winattn_delta_kernel(
-    KParams p, long long n_items, const OT* __restrict__ o, const bf16_t* __restrict__ d_o,
+    KParams p, const OT* __restrict__ o, const bf16_t* __restrict__ d_o,
     const float* __restrict__ lse, float* __restrict__ delta, float* __restrict__ lse2) {
   constexpr int kChunks = D / 8;
+  constexpr int kTokens = kThreads / kChunks;   // tokens per workgroup
+  const int blocks_per_pair = (p.T + kTokens - 1) / kTokens;
+  const int pair = blockIdx.x / blocks_per_pair;
+  const int t = (blockIdx.x - pair * blocks_per_pair) * kTokens + threadIdx.x / kChunks;
+  const int chunk = threadIdx.x % kChunks;
+  if (t >= p.T) return;   // whole token groups leave together (kChunks divides 64)
+  Window win;
+  win.init(p, pair);
   const long long plane = (long long)p.H * p.W;
-  for (long long gid = (long long)blockIdx.x * kThreads + threadIdx.x; gid < n_items * kChunks;
-       gid += (long long)gridDim.x * kThreads) {
-    const int chunk = (int)(gid % kChunks);
-    const long long item = gid / kChunks;       // (token, head), head fastest
-    const int head = (int)(item % p.nh);
-    const long long tok = item / p.nh;           // b * plane + y*W + x
-    const long long off = tok * p.o_tok + (long long)head * p.o_head + chunk * 8;
-    float a[8], b[8];
-    load8(o + off, a);
-    load8(d_o + off, b);
-    float acc = 0.f;
+  const int g = win.grid_index(p, t);
+  const long long off = ((long long)win.b * plane + g) * p.o_tok + (long long)win.head * p.o_head +
+                        chunk * 8;
+  float a[8], b[8];
+  load8(o + off, a);
+  load8(d_o + off, b);
+  float acc = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc = __builtin_fmaf(a[i], b[i], acc);
+  for (int i = 0; i < 8; ++i) acc = __builtin_fmaf(a[i], b[i], acc);
 #pragma unroll
-    for (int s = 1; s < kChunks; s <<= 1) acc += __shfl_xor(acc, s);
-    if (chunk == 0) {
-      const long long bidx = tok / plane;
-      const long long idx = (bidx * p.nh + head) * plane + (tok - bidx * plane);
-      delta[idx] = acc;
-      lse2[idx] = lse[idx] * kLog2e;
-    }
+  for (int s = 1; s < kChunks; s <<= 1) acc += __shfl_xor(acc, s);
+  if (chunk == 0) {
+    const long long idx = (long long)pair * p.T + t;
+    delta[idx] = acc;
+    lse2[idx] = lse[((long long)win.b * p.nh + win.head) * plane + g] * kLog2e;
   }
 }
 
@@ -78,7 +85,7 @@ __global__ __launch_bounds__(kThreads) void winattn_delta_kernel(
 // ----------------------------------------------------------------------------
 template <int D>
 constexpr size_t dq_smem_bytes(int T) {
-  return ((T * 4 + 15) & ~15) + 4 * Tile<D>::kBytes;
+  return table_bytes(T) + 4 * Tile<D>::kBytes;
 }
 
 template <int D, typename OutT>
@@ -87,9 +94,11 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
     const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
     const float* __restrict__ delta, const float* __restrict__ lse2v, OutT* __restrict__ dq) {
   using Tl = Tile<D>;
+  constexpr uint32_t kBuf = 2 * Tl::kBytes;   // one buffer: K tile, V tile
   extern __shared__ __align__(16) unsigned char smem[];
   int* tok_grid = reinterpret_cast<int*>(smem);
-  const uint32_t tiles = lds_address(smem) + ((p.T * 4 + 15) & ~15);
+  const uint32_t table = lds_address(smem);
+  const uint32_t tiles = table + table_bytes(p.T);
 
   int pair, qt;
   if (!block_to_work(p, pair, qt)) return;
@@ -102,13 +111,9 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qi = lane & 31, g = lane >> 5;
-  const int T = p.T;
   const long long plane = (long long)p.H * p.W;
   const long long qkv_base = ((long long)win.b * plane) * p.qkv_tok + (long long)win.head * p.qkv_head;
   const long long o_base = ((long long)win.b * plane) * p.o_tok + (long long)win.head * p.o_head;
-  const long long stat_base = ((long long)win.b * p.nh + win.head) * plane;
-  const bf16_t* kb = k + qkv_base;
-  const bf16_t* vb = v + qkv_base;
 
   Ranges rg;
   rg.init(win, qt, wave, qi);
@@ -117,8 +122,11 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
 
   const int kt_begin = rg.wg_lo / kStream;
   const int kt_end = (rg.wg_hi + kStream - 1) / kStream;
-  Tl::fill_async(tiles, kb, p.qkv_tok, tok_grid, kt_begin * kStream, T, wave, lane);
-  Tl::fill_async(tiles + Tl::kBytes, vb, p.qkv_tok, tok_grid, kt_begin * kStream, T, wave, lane);
+  typename Tl::Filler kfill, vfill;
+  kfill.init(k + qkv_base, p.qkv_tok, table, wave, lane);
+  vfill.init(v + qkv_base, p.qkv_tok, table, wave, lane);
+  kfill.fill(tiles, kt_begin * kStream);
+  vfill.fill(tiles + Tl::kBytes, kt_begin * kStream);
 
   bf16x8 qreg[D / 16], doreg[D / 16];
   {
@@ -130,10 +138,10 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
       doreg[kk] = *reinterpret_cast<const bf16x8*>(dorow + kk * 16);
     }
   }
-  float lse2 = lse2v[stat_base + q_grid];
-  float delta_q = delta[stat_base + q_grid];
+  float lse2 = lse2v[(long long)pair * p.T + rg.tok];
+  float delta_q = delta[(long long)pair * p.T + rg.tok];
   typename Tl::Lanes la;
-  la.init(lane);
+  la.init(tiles, lane);
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk) {
     settle(qreg[kk]);
@@ -148,56 +156,69 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
 
-  for (int kt = kt_begin; kt < kt_end; ++kt) {
-    const uint32_t buf = tiles + ((kt - kt_begin) & 1) * (2 * Tl::kBytes);
+  auto sub_block = [&](auto off, int sub_lo) {
+    constexpr uint32_t kOff = decltype(off)::value;
+    if (rg.skip(sub_lo)) return;
+    // operand reads first, products after: LDS latency hides behind the MFMA pipeline
+    bf16x8 ka[D / 16], va[D / 16], kta[D / 32][2];
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      ka[kk] = Tl::read_rm(la.rm[kk] + kOff);
+      va[kk] = Tl::read_rm(la.rm[kk] + kOff + Tl::kBytes);
+    }
+#pragma unroll
+    for (int cb = 0; cb < D / 32; ++cb)
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+        kta[cb][c] = Tl::read_tr(la.tr[cb][0] + kOff + c * Tl::kGroupBytes,
+                                 la.tr[cb][1] + kOff + c * Tl::kGroupBytes);
+    f32x16 s, dp;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      s = mfma32(ka[kk], qreg[kk], s);
+      dp = mfma32(va[kk], doreg[kk], dp);
+    }
+    if (!rg.mask_free(sub_lo)) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int kidx = sub_lo + acc_row(i, g);
+        if (kidx < lo_q || kidx >= hi_q) s[i] = -INFINITY;
+      }
+    }
+    float ds[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.scale_log2, -lse2));
+      ds[i] = pr * (dp[i] - delta_q);
+    }
+    union { u32x4 u; bf16x8 h; } dsb[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dsb[c].u[e] = pack_bf16(ds[8 * c + 2 * e], ds[8 * c + 2 * e + 1]);
+#pragma unroll
+    for (int cb = 0; cb < D / 32; ++cb)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) acc[cb] = mfma32(kta[cb][c], dsb[c].h, acc[cb]);
+  };
+
+  auto tile_step = [&](auto parity, int kt) {
+    constexpr uint32_t kP = decltype(parity)::value;
     wait_async_loads();
     __syncthreads();
     if (kt + 1 < kt_end) {
-      const uint32_t nxt = tiles + ((kt + 1 - kt_begin) & 1) * (2 * Tl::kBytes);
-      Tl::fill_async(nxt, kb, p.qkv_tok, tok_grid, (kt + 1) * kStream, T, wave, lane);
-      Tl::fill_async(nxt + Tl::kBytes, vb, p.qkv_tok, tok_grid, (kt + 1) * kStream, T, wave, lane);
+      kfill.fill(tiles + (1 - kP) * kBuf, (kt + 1) * kStream);
+      vfill.fill(tiles + (1 - kP) * kBuf + Tl::kBytes, (kt + 1) * kStream);
     }
-    if (!rg.wave_active) continue;
-#pragma unroll
-    for (int kb2 = 0; kb2 < kStream / 32; ++kb2) {
-      const int sub_lo = kt * kStream + kb2 * 32;
-      if (rg.skip(sub_lo)) continue;
-      const uint32_t ksub = buf + kb2 * Tl::kSubBytes;
-      const uint32_t vsub = buf + Tl::kBytes + kb2 * Tl::kSubBytes;
-      f32x16 s, dp;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
-#pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
-        s = mfma32(Tl::read_rm(ksub + la.rm[kk]), qreg[kk], s);
-        dp = mfma32(Tl::read_rm(vsub + la.rm[kk]), doreg[kk], dp);
-      }
-      if (!rg.mask_free(sub_lo)) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int kidx = sub_lo + acc_row(i, g);
-          if (kidx < lo_q || kidx >= hi_q) s[i] = -INFINITY;
-        }
-      }
-      float ds[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.scale_log2, -lse2));
-        ds[i] = pr * (dp[i] - delta_q);
-      }
-      union { u32x4 u; bf16x8 h; } dsb[2];
-#pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) dsb[c].u[e] = pack_bf16(ds[8 * c + 2 * e], ds[8 * c + 2 * e + 1]);
-#pragma unroll
-      for (int cb = 0; cb < D / 32; ++cb)
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          const uint32_t grp = ksub + c * (16 * D * 2);
-          acc[cb] = mfma32(Tl::read_tr(grp + la.tr[cb][0], grp + la.tr[cb][1]), dsb[c].h, acc[cb]);
-        }
-    }
+    if (!rg.wave_active) return;
+    sub_block(Const<kP * kBuf>{}, kt * kStream);
+    sub_block(Const<kP * kBuf + Tl::kSubBytes>{}, kt * kStream + 32);
+  };
+  for (int kt = kt_begin; kt < kt_end; kt += 2) {
+    tile_step(Const<0>{}, kt);
+    if (kt + 1 < kt_end) tile_step(Const<1>{}, kt + 1);
   }
 
   if (!rg.valid) return;
@@ -217,20 +238,22 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
 // ----------------------------------------------------------------------------
 template <int D>
 constexpr size_t dkdv_smem_bytes(int T) {
-  return ((T * 4 + 15) & ~15) + 2 * (2 * Tile<D>::kBytes + 2 * kStream * 4);
+  return table_bytes(T) + 2 * (2 * Tile<D>::kBytes + 2 * kStream * 4);
 }
 
 template <int D, typename OutT>
-__global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
+__global__ __launch_bounds__(kThreads, D == 128 ? 1 : 2) void winattn_dkdv_kernel(
     KParams p, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
     const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
     const float* __restrict__ delta, const float* __restrict__ lse2v, OutT* __restrict__ dk,
     OutT* __restrict__ dv) {
   using Tl = Tile<D>;
-  constexpr uint32_t kBufBytes = 2 * Tl::kBytes + 2 * kStream * 4;
+  constexpr uint32_t kStat = 2 * Tl::kBytes;            // offset of the statistics in a buffer
+  constexpr uint32_t kBuf = kStat + 2 * kStream * 4;    // Q tile, dO tile, LSE2[64], delta[64]
   extern __shared__ __align__(16) unsigned char smem[];
   int* tok_grid = reinterpret_cast<int*>(smem);
-  const uint32_t tiles = lds_address(smem) + ((p.T * 4 + 15) & ~15);
+  const uint32_t table = lds_address(smem);
+  const uint32_t tiles = table + table_bytes(p.T);
 
   int pair, kt;
   if (!block_to_work(p, pair, kt)) return;
@@ -243,13 +266,9 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ki = lane & 31, g = lane >> 5;
-  const int T = p.T;
   const long long plane = (long long)p.H * p.W;
   const long long qkv_base = ((long long)win.b * plane) * p.qkv_tok + (long long)win.head * p.qkv_head;
   const long long o_base = ((long long)win.b * plane) * p.o_tok + (long long)win.head * p.o_head;
-  const long long stat_base = ((long long)win.b * p.nh + win.head) * plane;
-  const bf16_t* qb = q + qkv_base;
-  const bf16_t* dob = d_o + o_base;
 
   Ranges rg;
   rg.init(win, kt, wave, ki);
@@ -257,15 +276,14 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
   const int lo_k = rg.lo, hi_k = rg.hi;
 
   // one streamed tile: Q, dO (all waves), LSE*log2e (wave 0), delta (wave 1)
+  typename Tl::Filler qfill, dofill;
+  qfill.init(q + qkv_base, p.qkv_tok, table, wave, lane);
+  dofill.init(d_o + o_base, p.o_tok, table, wave, lane);
+  const float* stat_src = (wave == 0 ? lse2v : delta) + (long long)pair * p.T + lane;
   auto fill = [&](uint32_t buf, int t0) {
-    Tl::fill_async(buf, qb, p.qkv_tok, tok_grid, t0, T, wave, lane);
-    Tl::fill_async(buf + Tl::kBytes, dob, p.o_tok, tok_grid, t0, T, wave, lane);
-    if (wave < 2) {
-      int t = t0 + lane;
-      t = t < T ? t : T - 1;
-      const float* src = (wave == 0 ? lse2v : delta) + stat_base + tok_grid[t];
-      async_copy4(src, buf + 2 * Tl::kBytes + wave * (kStream * 4));
-    }
+    qfill.fill(buf, t0);
+    dofill.fill(buf + Tl::kBytes, t0);
+    if (wave < 2) async_copy4(stat_src + t0, buf + kStat + wave * (kStream * 4));
   };
 
   const int qt_begin = rg.wg_lo / kStream;
@@ -283,7 +301,9 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
     }
   }
   typename Tl::Lanes la;
-  la.init(lane);
+  la.init(tiles, lane);
+  uint32_t stat_lane = tiles + kStat + 4 * g * 4;   // rows 8*vq + 4*g + (0..3) of a sub-block
+  settle(stat_lane);
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk) {
     settle(kreg[kk]);
@@ -296,67 +316,86 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) { dkacc[cb][i] = 0.f; dvacc[cb][i] = 0.f; }
 
-  for (int qt = qt_begin; qt < qt_end; ++qt) {
-    const uint32_t buf = tiles + ((qt - qt_begin) & 1) * kBufBytes;
+  // One 32-query block: kOff = compile-time LDS offset of its rows from buffer 0 /
+  // sub-block 0, kStatOff = the same for its statistics.
+  auto sub_block = [&](auto off, auto stat_off, int sub_lo) {
+    constexpr uint32_t kOff = decltype(off)::value;
+    constexpr uint32_t kStatOff = decltype(stat_off)::value;
+    if (rg.skip(sub_lo)) return;
+    // operand reads first, products after: LDS latency hides behind the MFMA pipeline
+    bf16x8 qa[D / 16], doa[D / 16], qta[D / 32][2], dota[D / 32][2];
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      qa[kk] = Tl::read_rm(la.rm[kk] + kOff);
+      doa[kk] = Tl::read_rm(la.rm[kk] + kOff + Tl::kBytes);
+    }
+    f32x4 l4[4], d4[4];
+#pragma unroll
+    for (int vq = 0; vq < 4; ++vq) {
+      l4[vq] = *reinterpret_cast<const AERIS_LDS f32x4*>(stat_lane + kStatOff + vq * 32);
+      d4[vq] = *reinterpret_cast<const AERIS_LDS f32x4*>(stat_lane + kStatOff + vq * 32 +
+                                                         kStream * 4);
+    }
+    // S[query, key] = Q K^T,  dP[query, key] = dO V^T: rows = streamed queries
+    f32x16 s, dp;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      s = mfma32(qa[kk], kreg[kk], s);
+      dp = mfma32(doa[kk], vreg[kk], dp);
+    }
+#pragma unroll
+    for (int cb = 0; cb < D / 32; ++cb)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        dota[cb][c] = Tl::read_tr(la.tr[cb][0] + kOff + Tl::kBytes + c * Tl::kGroupBytes,
+                                  la.tr[cb][1] + kOff + Tl::kBytes + c * Tl::kGroupBytes);
+        qta[cb][c] = Tl::read_tr(la.tr[cb][0] + kOff + c * Tl::kGroupBytes,
+                                 la.tr[cb][1] + kOff + c * Tl::kGroupBytes);
+      }
+    if (!rg.mask_free(sub_lo)) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int qidx = sub_lo + acc_row(i, g);
+        if (qidx < lo_k || qidx >= hi_k) s[i] = -INFINITY;
+      }
+    }
+    float pr[16], ds[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      pr[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.scale_log2, -l4[i >> 2][i & 3]));
+      ds[i] = pr[i] * (dp[i] - d4[i >> 2][i & 3]);
+    }
+    union { u32x4 u; bf16x8 h; } pb[2], dsb[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        pb[c].u[e] = pack_bf16(pr[8 * c + 2 * e], pr[8 * c + 2 * e + 1]);
+        dsb[c].u[e] = pack_bf16(ds[8 * c + 2 * e], ds[8 * c + 2 * e + 1]);
+      }
+#pragma unroll
+    for (int cb = 0; cb < D / 32; ++cb)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        dvacc[cb] = mfma32(dota[cb][c], pb[c].h, dvacc[cb]);
+        dkacc[cb] = mfma32(qta[cb][c], dsb[c].h, dkacc[cb]);
+      }
+  };
+
+  auto tile_step = [&](auto parity, int qt) {
+    constexpr uint32_t kP = decltype(parity)::value;
     wait_async_loads();
     __syncthreads();
-    if (qt + 1 < qt_end) fill(tiles + ((qt + 1 - qt_begin) & 1) * kBufBytes, (qt + 1) * kStream);
-    if (!rg.wave_active) continue;
-    const uint32_t stat = buf + 2 * Tl::kBytes;
-#pragma unroll
-    for (int qb2 = 0; qb2 < kStream / 32; ++qb2) {
-      const int sub_lo = qt * kStream + qb2 * 32;
-      if (rg.skip(sub_lo)) continue;
-      const uint32_t qsub = buf + qb2 * Tl::kSubBytes;
-      const uint32_t dosub = buf + Tl::kBytes + qb2 * Tl::kSubBytes;
-      // S[query, key] = Q K^T,  dP[query, key] = dO V^T: rows = streamed queries
-      f32x16 s, dp;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
-#pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
-        s = mfma32(Tl::read_rm(qsub + la.rm[kk]), kreg[kk], s);
-        dp = mfma32(Tl::read_rm(dosub + la.rm[kk]), vreg[kk], dp);
-      }
-      if (!rg.mask_free(sub_lo)) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int qidx = sub_lo + acc_row(i, g);
-          if (qidx < lo_k || qidx >= hi_k) s[i] = -INFINITY;
-        }
-      }
-      float pr[16], ds[16];
-#pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        const uint32_t at = stat + (qb2 * 32 + 8 * vq + 4 * g) * 4;
-        const f32x4 l4 = *reinterpret_cast<const AERIS_LDS f32x4*>(at);
-        const f32x4 d4 = *reinterpret_cast<const AERIS_LDS f32x4*>(at + kStream * 4);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * vq + e;
-          pr[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.scale_log2, -l4[e]));
-          ds[i] = pr[i] * (dp[i] - d4[e]);
-        }
-      }
-      union { u32x4 u; bf16x8 h; } pb[2], dsb[2];
-#pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          pb[c].u[e] = pack_bf16(pr[8 * c + 2 * e], pr[8 * c + 2 * e + 1]);
-          dsb[c].u[e] = pack_bf16(ds[8 * c + 2 * e], ds[8 * c + 2 * e + 1]);
-        }
-#pragma unroll
-      for (int cb = 0; cb < D / 32; ++cb)
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          const uint32_t off = c * (16 * D * 2);
-          dvacc[cb] = mfma32(Tl::read_tr(dosub + off + la.tr[cb][0], dosub + off + la.tr[cb][1]),
-                             pb[c].h, dvacc[cb]);
-          dkacc[cb] = mfma32(Tl::read_tr(qsub + off + la.tr[cb][0], qsub + off + la.tr[cb][1]),
-                             dsb[c].h, dkacc[cb]);
-        }
-    }
+    if (qt + 1 < qt_end) fill(tiles + (1 - kP) * kBuf, (qt + 1) * kStream);
+    if (!rg.wave_active) return;
+    sub_block(Const<kP * kBuf>{}, Const<kP * kBuf>{}, qt * kStream);
+    sub_block(Const<kP * kBuf + Tl::kSubBytes>{}, Const<kP * kBuf + 32 * 4>{}, qt * kStream + 32);
+  };
+  for (int qt = qt_begin; qt < qt_end; qt += 2) {
+    tile_step(Const<0>{}, qt);
+    if (qt + 1 < qt_end) tile_step(Const<1>{}, qt + 1);
   }
 
   if (!rg.valid) return;
@@ -390,15 +429,13 @@ static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const v
   const bf16_t* vp = static_cast<const bf16_t*>(v);
   const bf16_t* dop = static_cast<const bf16_t*>(d_o);
 
-  const long long n_items = (long long)kp.B * kp.H * kp.W * kp.nh;
   float* delta = workspace;
-  float* lse2 = workspace + n_items;
+  float* lse2 = workspace + stat_entries(kp);
   if (stages & 1u) {
-    const long long n_thr = n_items * (D / 8);
-    long long dblocks = (n_thr + kThreads - 1) / kThreads;
-    if (dblocks > 256 * 64) dblocks = 256 * 64;
+    constexpr int kTokens = kThreads / (D / 8);
+    const long long dblocks = (long long)kp.n_pairs * ((kp.T + kTokens - 1) / kTokens);
     hipLaunchKernelGGL((winattn_delta_kernel<D, OutT>), dim3((unsigned)dblocks), dim3(kThreads),
-                       0, stream, kp, n_items, static_cast<const OutT*>(o), dop, lse, delta, lse2);
+                       0, stream, kp, static_cast<const OutT*>(o), dop, lse, delta, lse2);
     if (hipGetLastError() != hipSuccess) return -1;
   }
 
@@ -423,6 +460,8 @@ static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const v
   }
   return 0;
 }
+
+size_t bwd_workspace_bytes(const KParams& kp) { return 2 * (size_t)stat_entries(kp) * sizeof(float); }
 
 int launch_bwd(const KParams& kp, int head_dim, bool out_f32, const void* q, const void* k,
                const void* v, const void* o, const float* lse, const void* d_o, void* dq,

@@ -1,6 +1,6 @@
 // Shared device-side pieces of the gfx950 shifted-window attention kernels:
 // kernel parameter block, window geometry (cyclic shift + partition + region
-// ordering), MFMA operand types, tile staging through LDS.
+// ordering), MFMA operand types, streamed LDS tiles.
 //
 // Window geometry follows the AERIS paper's Model Architecture section (square
 // windows, shifted on alternating layers) with the cyclic wrap of Fig. 2a; the
@@ -8,6 +8,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 namespace aeris {
 
@@ -21,11 +23,15 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+template <int N>
+using Const = std::integral_constant<int, N>;
+
 constexpr int kThreads = 256;      // 4 wavefronts of 64 lanes
 constexpr int kWaves = 4;
 constexpr int kResident = 128;     // tokens a workgroup keeps in registers (32 per wave)
 constexpr int kStream = 64;        // tokens per streamed LDS tile
 constexpr float kLazyRescale = 8.0f;  // log2 units a row maximum may lag behind
+constexpr float kLog2e = 1.4426950408889634f;
 
 // Host-filled launch parameters (plain data, passed by value).
 struct KParams {
@@ -41,6 +47,10 @@ struct KParams {
   long long qkv_tok, qkv_head;  // element strides of q,k,v,dq,dk,dv
   long long o_tok, o_head;      // element strides of o, dO
 };
+
+// Bytes of the per-window token table: one int per token, padded to a whole
+// streamed tile (the padding repeats the last token, so loads never need a clamp).
+__host__ __device__ inline int table_bytes(int T) { return ((T + kStream - 1) / kStream) * kStream * 4; }
 
 // ----------------------------------------------------------------------------
 // Workgroup id -> (pair, tile).  Hardware deals consecutive workgroup ids to
@@ -155,10 +165,13 @@ struct Ranges {
   __device__ __forceinline__ bool mask_free(int s) const { return s >= lo_max && s + 32 <= hi_min; }
 };
 
-// Fill the per-window table token -> y*W + x (in LDS).  Caller barriers.
+// Fill the per-window table token -> y*W + x (in LDS), padding included.
+// Caller barriers.
 __device__ __forceinline__ void build_token_table(const KParams& p, const Window& win,
                                                   int* tok_grid) {
-  for (int t = threadIdx.x; t < p.T; t += kThreads) tok_grid[t] = win.grid_index(p, t);
+  const int padded = table_bytes(p.T) / 4;
+  for (int t = threadIdx.x; t < padded; t += kThreads)
+    tok_grid[t] = win.grid_index(p, t < p.T ? t : p.T - 1);
 }
 
 // ----------------------------------------------------------------------------
@@ -208,7 +221,6 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // 4 consecutive chunks hit 16 different positions.
 // ----------------------------------------------------------------------------
 #define AERIS_LDS __attribute__((address_space(3)))
-#define AERIS_GLB __attribute__((address_space(1)))
 
 __device__ __forceinline__ uint32_t lds_address(const void* generic) {
   return (uint32_t)(uintptr_t)(AERIS_LDS const void*)generic;
@@ -246,6 +258,7 @@ struct Tile {
   static constexpr int NC = D / 8;                  // 16-byte chunks per token row
   static constexpr int kBytes = kStream * D * 2;
   static constexpr int kSubBytes = 32 * D * 2;      // 32-token sub-block
+  static constexpr int kGroupBytes = 16 * D * 2;    // 16-token group of a second product
   static constexpr int kFillPerWave = NC / kWaves;  // wave instructions per tile and wave
 
   __device__ __forceinline__ static int swz(int r) {
@@ -258,34 +271,49 @@ struct Tile {
     return (r * NC + (c ^ swz(r))) * 16;
   }
 
-  // Asynchronous fill of the tile at LDS byte address `tile` (wave-uniform)
-  // with tokens t0 .. t0+63 of one (batch, head); completion is tracked by
-  // vmcnt.  Tokens past the window's end re-read the last token (masked later).
-  __device__ __forceinline__ static void fill_async(uint32_t tile, const bf16_t* base,
-                                                    long long tok_stride, const int* tok_grid,
-                                                    int t0, int T, int wave, int lane) {
+  // Asynchronous tile fill.  Per lane and wave instruction i, the source is
+  //   base + table[t0 + row_i] * stride_bytes + chunk_i * 16
+  // (one LDS table read and one 64-bit multiply-add per 16 bytes moved).
+  struct Filler {
+    const char* src[kFillPerWave];   // tensor origin of this (batch, head) + lane's chunk
+    uint32_t tab;                    // LDS byte address of table[row of instruction 0]
+    uint32_t dst;                    // byte offset of this wave's first instruction in a tile
+    uint32_t stride_bytes;
+    static constexpr int kRowsPerInst = 64 / NC;
+
+    __device__ __forceinline__ void init(const bf16_t* origin, long long tok_stride,
+                                         uint32_t table_lds, int wave, int lane) {
+      stride_bytes = (uint32_t)(tok_stride * 2);
+      dst = wave * kFillPerWave * 1024;
+      tab = table_lds + (wave * kFillPerWave * kRowsPerInst + lane / NC) * 4;
 #pragma unroll
-    for (int i = 0; i < kFillPerWave; ++i) {
-      const int inst = wave * kFillPerWave + i;
-      const int slot = inst * 64 + lane;
-      const int r = slot / NC;
-      const int c = (slot % NC) ^ swz(r);
-      int t = t0 + r;
-      t = t < T ? t : T - 1;
-      const bf16_t* src = base + (long long)tok_grid[t] * tok_stride + c * 8;
-      async_copy16(src, tile + inst * 1024);
+      for (int i = 0; i < kFillPerWave; ++i) {
+        const int r = (wave * kFillPerWave + i) * kRowsPerInst + lane / NC;
+        const int c = (lane % NC) ^ swz(r);
+        src[i] = reinterpret_cast<const char*>(origin) + c * 16;
+      }
     }
-  }
+    // tile: LDS byte address (wave-uniform); t0: first token (multiple of kStream).
+    __device__ __forceinline__ void fill(uint32_t tile, int t0) const {
+      const uint32_t row0 = tab + t0 * 4;
+#pragma unroll
+      for (int i = 0; i < kFillPerWave; ++i) {
+        const uint32_t g =
+            *reinterpret_cast<const AERIS_LDS uint32_t*>(row0 + i * kRowsPerInst * 4);
+        async_copy16(src[i] + (unsigned long long)g * stride_bytes, tile + dst + i * 1024);
+      }
+    }
+  };
 
-  // Per-lane byte offsets (tile-relative, sub-block 0) of the operand reads.
+  // Per-lane LDS byte addresses (buffer 0, sub-block 0) of the operand reads.
   struct Lanes {
-    int rm[D / 16];        // row-major: contraction block kk
-    int tr[D / 32][2];     // transposed: channel block cb, first/second four tokens
+    uint32_t rm[D / 16];        // row-major: contraction block kk
+    uint32_t tr[D / 32][2];     // transposed: channel block cb, first/second four tokens
 
-    __device__ __forceinline__ void init(int lane) {
+    __device__ __forceinline__ void init(uint32_t tile0, int lane) {
       const int row = lane & 31, g = lane >> 5;
 #pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) rm[kk] = chunk_offset(row, 2 * kk + g);
+      for (int kk = 0; kk < D / 16; ++kk) rm[kk] = tile0 + chunk_offset(row, 2 * kk + g);
       const int j = lane & 15, blk = lane >> 4;
 #pragma unroll
       for (int cb = 0; cb < D / 32; ++cb)
@@ -293,8 +321,16 @@ struct Tile {
         for (int h = 0; h < 2; ++h) {
           const int r = 8 * h + 4 * (blk >> 1) + (j >> 2);
           const int c = 4 * cb + 2 * (blk & 1) + ((j & 3) >> 1);
-          tr[cb][h] = chunk_offset(r, c) + (j & 1) * 8;
+          tr[cb][h] = tile0 + chunk_offset(r, c) + (j & 1) * 8;
         }
+      // keep the finished addresses in registers (reads then need no VALU at all)
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk) settle(rm[kk]);
+#pragma unroll
+      for (int cb = 0; cb < D / 32; ++cb) {
+        settle(tr[cb][0]);
+        settle(tr[cb][1]);
+      }
     }
   };
 

@@ -18,7 +18,7 @@ namespace aeris {
 
 template <int D>
 constexpr size_t fwd_smem_bytes(int T) {
-  return ((T * 4 + 15) & ~15) + 4 * Tile<D>::kBytes;   // table + 2 buffers x (K, V)
+  return table_bytes(T) + 4 * Tile<D>::kBytes;   // table + 2 buffers x (K, V)
 }
 
 template <int D, typename OutT>
@@ -26,9 +26,11 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
     KParams p, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
     const bf16_t* __restrict__ v, OutT* __restrict__ o, float* __restrict__ lse) {
   using Tl = Tile<D>;
+  constexpr uint32_t kBuf = 2 * Tl::kBytes;   // one buffer: K tile, V tile
   extern __shared__ __align__(16) unsigned char smem[];
   int* tok_grid = reinterpret_cast<int*>(smem);
-  const uint32_t tiles = lds_address(smem) + ((p.T * 4 + 15) & ~15);   // [buf][K,V]
+  const uint32_t table = lds_address(smem);
+  const uint32_t tiles = table + table_bytes(p.T);
 
   int pair, qt;
   if (!block_to_work(p, pair, qt)) return;
@@ -41,12 +43,9 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qi = lane & 31, g = lane >> 5;
-  const int T = p.T;
 
   const long long plane = (long long)p.H * p.W;
   const long long qkv_base = ((long long)win.b * plane) * p.qkv_tok + (long long)win.head * p.qkv_head;
-  const bf16_t* kb = k + qkv_base;
-  const bf16_t* vb = v + qkv_base;
 
   // ---- this lane's query ----------------------------------------------------
   Ranges rg;
@@ -56,8 +55,11 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
 
   const int kt_begin = rg.wg_lo / kStream;
   const int kt_end = (rg.wg_hi + kStream - 1) / kStream;
-  Tl::fill_async(tiles, kb, p.qkv_tok, tok_grid, kt_begin * kStream, T, wave, lane);
-  Tl::fill_async(tiles + Tl::kBytes, vb, p.qkv_tok, tok_grid, kt_begin * kStream, T, wave, lane);
+  typename Tl::Filler kfill, vfill;
+  kfill.init(k + qkv_base, p.qkv_tok, table, wave, lane);
+  vfill.init(v + qkv_base, p.qkv_tok, table, wave, lane);
+  kfill.fill(tiles, kt_begin * kStream);
+  vfill.fill(tiles + Tl::kBytes, kt_begin * kStream);
 
   bf16x8 qreg[D / 16];
   {
@@ -67,7 +69,7 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
       qreg[kk] = *reinterpret_cast<const bf16x8*>(qrow + kk * 16);
   }
   typename Tl::Lanes la;
-  la.init(lane);
+  la.init(tiles, lane);
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk) settle(qreg[kk]);
 
@@ -79,74 +81,92 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
   float m_run = -INFINITY;   // running (lagging) row maximum, log2 domain
   float l_run = 0.f;         // this lane's share of the row sum
 
-  for (int kt = kt_begin; kt < kt_end; ++kt) {
-    const uint32_t buf = tiles + ((kt - kt_begin) & 1) * (2 * Tl::kBytes);
-    wait_async_loads();      // this wave's part of tile kt has landed
-    __syncthreads();         // ... everyone's has; and everyone is done with tile kt-1
-    if (kt + 1 < kt_end) {   // next tile flies during the math, into the other buffer
-      const uint32_t nxt = tiles + ((kt + 1 - kt_begin) & 1) * (2 * Tl::kBytes);
-      Tl::fill_async(nxt, kb, p.qkv_tok, tok_grid, (kt + 1) * kStream, T, wave, lane);
-      Tl::fill_async(nxt + Tl::kBytes, vb, p.qkv_tok, tok_grid, (kt + 1) * kStream, T, wave, lane);
-    }
-    if (!rg.wave_active) continue;
+  // One 32-key block at compile-time LDS offset kOff from buffer 0 / sub-block 0:
+  // every operand address is a per-lane register plus an immediate.
+  auto sub_block = [&](auto off, int sub_lo) {
+    constexpr uint32_t kOff = decltype(off)::value;
+    if (rg.skip(sub_lo)) return;   // wave-uniform
+    // ---- operand reads first, products after: LDS latency hides behind the MFMA
+    //      pipeline; the V operands land during the softmax ------------------------
+    bf16x8 ka[D / 16], va[D / 32][2];
 #pragma unroll
-    for (int kb2 = 0; kb2 < kStream / 32; ++kb2) {
-      const int sub_lo = kt * kStream + kb2 * 32;
-      if (rg.skip(sub_lo)) continue;   // wave-uniform
-      const uint32_t ksub = buf + kb2 * Tl::kSubBytes;
-      const uint32_t vsub = buf + Tl::kBytes + kb2 * Tl::kSubBytes;
-      // ---- S^T = K Q^T -------------------------------------------------------
-      f32x16 s;
+    for (int kk = 0; kk < D / 16; ++kk) ka[kk] = Tl::read_rm(la.rm[kk] + kOff);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s[i] = 0.f;
+    for (int cb = 0; cb < D / 32; ++cb)
 #pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) s = mfma32(Tl::read_rm(ksub + la.rm[kk]), qreg[kk], s);
-      // ---- mask --------------------------------------------------------------
-      if (!rg.mask_free(sub_lo)) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int kidx = sub_lo + acc_row(i, g);
-          if (kidx < lo_q || kidx >= hi_q) s[i] = -INFINITY;
-        }
+      for (int c = 0; c < 2; ++c) {
+        constexpr uint32_t kV = kOff + Tl::kBytes;
+        va[cb][c] = Tl::read_tr(la.tr[cb][0] + kV + c * Tl::kGroupBytes,
+                                la.tr[cb][1] + kV + c * Tl::kGroupBytes);
       }
-      // ---- online softmax (log2 domain, lagging maximum) ----------------------
-      float mx = s[0];
+    // ---- S^T = K Q^T ---------------------------------------------------------
+    f32x16 s;
 #pragma unroll
-      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
-      mx = wave_half_max(mx) * p.scale_log2;
-      const bool grow = mx > m_run + kLazyRescale;
-      if (__builtin_expect(__any(grow), 0)) {
-        const float alpha = grow ? __builtin_amdgcn_exp2f(m_run - mx) : 1.f;
-        m_run = grow ? mx : m_run;
-        l_run *= alpha;
+    for (int i = 0; i < 16; ++i) s[i] = 0.f;
 #pragma unroll
-        for (int cb = 0; cb < D / 32; ++cb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) oacc[cb][i] *= alpha;
-      }
-      const float m_sub = m_run == -INFINITY ? 0.f : m_run;
-      float pv[16];
-      float psum = 0.f;
+    for (int kk = 0; kk < D / 16; ++kk) s = mfma32(ka[kk], qreg[kk], s);
+    // ---- mask ----------------------------------------------------------------
+    if (!rg.mask_free(sub_lo)) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.scale_log2, -m_sub));
-        psum += pv[i];
+        const int kidx = sub_lo + acc_row(i, g);
+        if (kidx < lo_q || kidx >= hi_q) s[i] = -INFINITY;
       }
-      l_run += psum;
-      // ---- O^T += V^T P^T ------------------------------------------------------
-      union { u32x4 u; bf16x8 h; } pb[2];
+    }
+    // ---- online softmax (log2 domain, lagging maximum) --------------------------
+    float mx = s[0];
 #pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) pb[c].u[e] = pack_bf16(pv[8 * c + 2 * e], pv[8 * c + 2 * e + 1]);
+    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
+    mx = wave_half_max(mx) * p.scale_log2;
+    const bool grow = mx > m_run + kLazyRescale;
+    if (__builtin_expect(__any(grow), 0)) {
+      const float alpha = grow ? __builtin_amdgcn_exp2f(m_run - mx) : 1.f;
+      m_run = grow ? mx : m_run;
+      l_run *= alpha;
 #pragma unroll
       for (int cb = 0; cb < D / 32; ++cb)
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          const uint32_t grp = vsub + c * (16 * D * 2);   // 16-token group
-          oacc[cb] = mfma32(Tl::read_tr(grp + la.tr[cb][0], grp + la.tr[cb][1]), pb[c].h, oacc[cb]);
-        }
+        for (int i = 0; i < 16; ++i) oacc[cb][i] *= alpha;
     }
+    const float m_sub = m_run == -INFINITY ? 0.f : m_run;
+    float pv[16];
+    float psum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.scale_log2, -m_sub));
+      psum += pv[i];
+    }
+    l_run += psum;
+    // ---- O^T += V^T P^T ----------------------------------------------------------
+    union { u32x4 u; bf16x8 h; } pb[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pb[c].u[e] = pack_bf16(pv[8 * c + 2 * e], pv[8 * c + 2 * e + 1]);
+#pragma unroll
+    for (int cb = 0; cb < D / 32; ++cb)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) oacc[cb] = mfma32(va[cb][c], pb[c].h, oacc[cb]);
+  };
+
+  // One streamed tile held in buffer kP (compile time); the next one flies into
+  // the other buffer during the math.  One barrier per tile: it publishes tile
+  // kt and retires the readers of tile kt-1, whose buffer the new fill reuses.
+  auto tile_step = [&](auto parity, int kt) {
+    constexpr uint32_t kP = decltype(parity)::value;
+    wait_async_loads();
+    __syncthreads();
+    if (kt + 1 < kt_end) {
+      kfill.fill(tiles + (1 - kP) * kBuf, (kt + 1) * kStream);
+      vfill.fill(tiles + (1 - kP) * kBuf + Tl::kBytes, (kt + 1) * kStream);
+    }
+    if (!rg.wave_active) return;
+    sub_block(Const<kP * kBuf>{}, kt * kStream);
+    sub_block(Const<kP * kBuf + Tl::kSubBytes>{}, kt * kStream + 32);
+  };
+  for (int kt = kt_begin; kt < kt_end; kt += 2) {
+    tile_step(Const<0>{}, kt);
+    if (kt + 1 < kt_end) tile_step(Const<1>{}, kt + 1);
   }
 
   // ---- epilogue: normalise, un-shift/un-partition store -----------------------

@@ -11,6 +11,9 @@ int launch_fwd(const KParams& kp, int head_dim, bool out_f32, const void* q, con
 
 int launch_bwd(const KParams& kp, int head_dim, bool out_f32, const void* q, const void* k,
                const void* v, const void* o, const float* lse, const void* d_o, void* dq,
-               void* dk, void* dv, float* delta, hipStream_t stream, unsigned stages);
+               void* dk, void* dv, float* workspace, hipStream_t stream, unsigned stages);
+
+// Bytes of device workspace launch_bwd needs for these parameters.
+size_t bwd_workspace_bytes(const KParams& kp);
 
 }  // namespace aeris

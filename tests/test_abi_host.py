@@ -67,7 +67,7 @@ def test_null_and_misaligned_pointers_rejected_before_launch():
     args = [fake] * 10
     assert lib.aeris_winattn_bwd(ctypes.byref(p), *args[:9], None, 1 << 30, None) == -1
     need = B.aeris_winattn_bwd_workspace_bytes(p)
-    assert need == 2 * 1 * 4 * 64 * 128 * 4
+    assert need == 2 * (1 * 4 * 64 * 128 + 64) * 4
     assert lib.aeris_winattn_bwd(ctypes.byref(p), *args, need - 1, None) == -8
     bad = B.make_params(**dict(good(), win=(7, 8)))
     assert B.aeris_winattn_bwd_workspace_bytes(bad) == 0
