@@ -58,6 +58,11 @@ __global__ __launch_bounds__(kThreads) void winattn_delta_kernel(
   const int pair = blockIdx.x / blocks_per_pair;
   const int t = (blockIdx.x - pair * blocks_per_pair) * kTokens + threadIdx.x / kChunks;
   const int chunk = threadIdx.x % kChunks;
+  if (blockIdx.x == 0 && threadIdx.x < kStream) {
+    // padding behind the last pair: streamed tiles read up to 63 entries past a window's end
+    delta[(long long)p.n_pairs * p.T + threadIdx.x] = 0.f;
+    lse2[(long long)p.n_pairs * p.T + threadIdx.x] = 0.f;
+  }
   if (t >= p.T) return;   // whole token groups leave together (kChunks divides 64)
   Window win;
   win.init(p, pair);
@@ -156,7 +161,7 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
 
-  auto sub_block = [&](auto off, int sub_lo) {
+  auto sub_block = [&](auto off, int sub_lo) __attribute__((always_inline)) {
     constexpr uint32_t kOff = decltype(off)::value;
     if (rg.skip(sub_lo)) return;
     // operand reads first, products after: LDS latency hides behind the MFMA pipeline
@@ -204,7 +209,7 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
       for (int c = 0; c < 2; ++c) acc[cb] = mfma32(kta[cb][c], dsb[c].h, acc[cb]);
   };
 
-  auto tile_step = [&](auto parity, int kt) {
+  auto tile_step = [&](auto parity, int kt) __attribute__((always_inline)) {
     constexpr uint32_t kP = decltype(parity)::value;
     wait_async_loads();
     __syncthreads();
@@ -280,7 +285,7 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 1 : 2) void winattn_dkdv_kerne
   qfill.init(q + qkv_base, p.qkv_tok, table, wave, lane);
   dofill.init(d_o + o_base, p.o_tok, table, wave, lane);
   const float* stat_src = (wave == 0 ? lse2v : delta) + (long long)pair * p.T + lane;
-  auto fill = [&](uint32_t buf, int t0) {
+  auto fill = [&](uint32_t buf, int t0) __attribute__((always_inline)) {
     qfill.fill(buf, t0);
     dofill.fill(buf + Tl::kBytes, t0);
     if (wave < 2) async_copy4(stat_src + t0, buf + kStat + wave * (kStream * 4));
@@ -318,7 +323,7 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 1 : 2) void winattn_dkdv_kerne
 
   // One 32-query block: kOff = compile-time LDS offset of its rows from buffer 0 /
   // sub-block 0, kStatOff = the same for its statistics.
-  auto sub_block = [&](auto off, auto stat_off, int sub_lo) {
+  auto sub_block = [&](auto off, auto stat_off, int sub_lo) __attribute__((always_inline)) {
     constexpr uint32_t kOff = decltype(off)::value;
     constexpr uint32_t kStatOff = decltype(stat_off)::value;
     if (rg.skip(sub_lo)) return;
@@ -384,7 +389,7 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 1 : 2) void winattn_dkdv_kerne
       }
   };
 
-  auto tile_step = [&](auto parity, int qt) {
+  auto tile_step = [&](auto parity, int qt) __attribute__((always_inline)) {
     constexpr uint32_t kP = decltype(parity)::value;
     wait_async_loads();
     __syncthreads();
@@ -449,7 +454,11 @@ static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const v
                        static_cast<OutT*>(dq));
     if (hipGetLastError() != hipSuccess) return -1;
   }
-  if (stages & 4u) {
+  if ((stages & 4u) && D == 128) {
+    if (launch_dkdv_pipe128(kp, std::is_same<OutT, float>::value, q, k, v, d_o, delta, lse2, dk,
+                            dv, stream) != 0)
+      return -1;
+  } else if (stages & 4u) {
     const size_t smem = dkdv_smem_bytes<D>(kp.T);
     auto kern = winattn_dkdv_kernel<D, OutT>;
     if (!allow_smem(kern, smem)) return -1;

@@ -233,14 +233,14 @@ __device__ __forceinline__ uint32_t lds_address(const void* generic) {
 __device__ __forceinline__ void async_copy16(const void* src, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
                :
-               : "v"(src), "s"(lds_base)
+               : "v"(src), "s"(__builtin_amdgcn_readfirstlane(lds_base))
                : "memory");
 }
 // 4 bytes per lane: lane l's dword lands at lds_base + 4*l.
 __device__ __forceinline__ void async_copy4(const void* src, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off"
                :
-               : "v"(src), "s"(lds_base)
+               : "v"(src), "s"(__builtin_amdgcn_readfirstlane(lds_base))
                : "memory");
 }
 __device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }

@@ -1,0 +1,345 @@
+// dK/dV kernel, software-pipelined variant (used for head_dim 128, where the
+// two 128x32 accumulators leave room for only one wave per SIMD, so nothing but
+// the instruction order inside the wave can overlap matrix and vector work).
+//
+// Same mathematics and data flow as winattn_dkdv_kernel (see winattn_bwd.hip):
+// keys resident, queries streamed through LDS tiles, S = Q K^T and dP = dO V^T
+// by row-major reads, dV^T += dO^T P and dK^T += Q^T dS by transposing reads.
+// What differs is the schedule.  Per 32-query block j:
+//     stage A(j):  16 MFMA   logits S_j, dP_j
+//     stage B(j):  ~100 VALU P_j = exp2(S_j*c - LSE2), dS_j = P_j (dP_j - delta)
+//     stage C(j):  16 MFMA   dV^T += dO_j^T P_j, dK^T += Q_j^T dS_j
+// and the instruction stream is A(j+1) interleaved with B(j) -- one MFMA, then
+// one logit's worth of vector work -- followed by C(j).  On gfx950 a 32x32x16
+// MFMA keeps the matrix pipe busy for 32 cycles but blocks instruction issue for
+// only about half of that, so the vector work of B rides under the MFMAs of A.
+// Three LDS buffers: tile t+2 streams in while A reads tile t+1 and C reads t.
+#include "winattn_common.hpp"
+#include "winattn_launch.hpp"
+
+// Optional stage timing (development aid, off by default): -DAERIS_STAGE_TIMING makes one
+// wave of one workgroup accumulate the 100 MHz wall clock per pipeline stage into
+// aeris_stage_ticks[], which a test harness reads back with hipMemcpyFromSymbol.
+#ifdef AERIS_STAGE_TIMING
+__device__ unsigned long long aeris_stage_ticks[16];
+#define AERIS_TICK_DECL                                                              \
+  const bool tick_on = blockIdx.x == 8 * 40 + 3 && threadIdx.x == 0;                 \
+  unsigned long long tick_last = wall_clock64(), tick_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#define AERIS_TICK(i)                                 \
+  if (tick_on) {                                      \
+    const unsigned long long t = wall_clock64();      \
+    tick_acc[i] += t - tick_last;                     \
+    tick_last = t;                                    \
+  }
+#define AERIS_TICK_FLUSH \
+  if (tick_on)           \
+    for (int i = 0; i < 8; ++i) aeris_stage_ticks[i] = tick_acc[i];
+#else
+#define AERIS_TICK_DECL
+#define AERIS_TICK(i)
+#define AERIS_TICK_FLUSH
+#endif
+
+namespace aeris {
+
+template <int D>
+constexpr size_t dkdv_pipe_smem_bytes(int T) {
+  return table_bytes(T) + 3 * (2 * Tile<D>::kBytes + 2 * kStream * 4);
+}
+
+template <int D, typename OutT>
+__global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
+    KParams p, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+    const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
+    const float* __restrict__ delta, const float* __restrict__ lse2v, OutT* __restrict__ dk,
+    OutT* __restrict__ dv) {
+  using Tl = Tile<D>;
+  constexpr uint32_t kStat = 2 * Tl::kBytes;            // offset of the statistics in a buffer
+  constexpr uint32_t kBuf = kStat + 2 * kStream * 4;    // Q tile, dO tile, LSE2[64], delta[64]
+  constexpr int kNK = D / 16;                           // contraction blocks of the first products
+  constexpr int kNA = 2 * kNK;                          // MFMAs of stage A
+  constexpr int kNC = 4 * (D / 32);                     // MFMAs of stage C
+  extern __shared__ __align__(16) unsigned char smem[];
+  int* tok_grid = reinterpret_cast<int*>(smem);
+  const uint32_t table = lds_address(smem);
+  const uint32_t tiles = table + table_bytes(p.T);
+
+  int pair, kt;
+  if (!block_to_work(p, pair, kt)) return;
+
+  Window win;
+  win.init(p, pair);
+  build_token_table(p, win, tok_grid);
+  __syncthreads();
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ki = lane & 31, g = lane >> 5;
+  const long long plane = (long long)p.H * p.W;
+  const long long qkv_base = ((long long)win.b * plane) * p.qkv_tok + (long long)win.head * p.qkv_head;
+  const long long o_base = ((long long)win.b * plane) * p.o_tok + (long long)win.head * p.o_head;
+
+  Ranges rg;
+  rg.init(win, kt, wave, ki);
+  const int k_grid = tok_grid[rg.tok];
+  const int lo_k = rg.lo, hi_k = rg.hi;
+
+  typename Tl::Filler qfill, dofill;
+  qfill.init(q + qkv_base, p.qkv_tok, table, wave, lane);
+  dofill.init(d_o + o_base, p.o_tok, table, wave, lane);
+  const float* stat_src = (wave == 0 ? lse2v : delta) + (long long)pair * p.T + lane;
+  auto fill = [&](uint32_t buf, int t0) __attribute__((always_inline)) {
+    qfill.fill(buf, t0);
+    dofill.fill(buf + Tl::kBytes, t0);
+    if (wave < 2) async_copy4(stat_src + t0, buf + kStat + wave * (kStream * 4));
+  };
+
+  const int qt_begin = rg.wg_lo / kStream;
+  const int qt_end = (rg.wg_hi + kStream - 1) / kStream;
+  fill(tiles, qt_begin * kStream);
+
+  bf16x8 kreg[kNK], vreg[kNK];
+  {
+    const bf16_t* krow = k + qkv_base + (long long)k_grid * p.qkv_tok + 8 * g;
+    const bf16_t* vrow = v + qkv_base + (long long)k_grid * p.qkv_tok + 8 * g;
+#pragma unroll
+    for (int kk = 0; kk < kNK; ++kk) {
+      kreg[kk] = *reinterpret_cast<const bf16x8*>(krow + kk * 16);
+      vreg[kk] = *reinterpret_cast<const bf16x8*>(vrow + kk * 16);
+    }
+  }
+  // Per-lane LDS addresses.  `rm` (row-major reads, stage A) points into the
+  // buffer of the tile stage A works on; `tr` (transposing reads, stage C) and
+  // `st` (statistics, stage B) into the buffer of the tile stages B and C work
+  // on.  They advance by one buffer per tile, independently.
+  typename Tl::Lanes la;
+  la.init(tiles, lane);
+  uint32_t st = tiles + kStat + 4 * g * 4;   // rows 8*vq + 4*g + (0..3) of a sub-block
+  settle(st);
+#pragma unroll
+  for (int kk = 0; kk < kNK; ++kk) {
+    settle(kreg[kk]);
+    settle(vreg[kk]);
+  }
+
+  f32x16 dkacc[D / 32], dvacc[D / 32];
+#pragma unroll
+  for (int cb = 0; cb < D / 32; ++cb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { dkacc[cb][i] = 0.f; dvacc[cb][i] = 0.f; }
+
+  f32x16 s, dp;                                   // logits of the block stage B consumes next
+  union Packed { u32x4 u; bf16x8 h; };
+  Packed pb[2], dsb[2];                           // P, dS of the block stage C consumes
+
+  // operand i of stage A: even -> Q rows, odd -> dO rows, contraction block i/2
+  auto a_operand = [&](int i, uint32_t sub) __attribute__((always_inline)) {
+    return Tl::read_rm(la.rm[i >> 1] + sub + ((i & 1) ? Tl::kBytes : 0));
+  };
+  // operand i of stage C: channel block i/4, 16-query group (i/2)%2, even -> dO^T, odd -> Q^T
+  auto c_operand = [&](int i, uint32_t sub) __attribute__((always_inline)) {
+    const int cb = i >> 2, c = (i >> 1) & 1;
+    const uint32_t off = sub + c * Tl::kGroupBytes + ((i & 1) ? 0 : Tl::kBytes);
+    return Tl::read_tr(la.tr[cb][0] + off, la.tr[cb][1] + off);
+  };
+
+  // Stage A alone (pipeline prologue).
+  auto stage_a = [&](uint32_t sub) __attribute__((always_inline)) {
+    bf16x8 op[kNA];
+#pragma unroll
+    for (int i = 0; i < kNA; ++i) op[i] = a_operand(i, sub);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+#pragma unroll
+    for (int i = 0; i < kNA; ++i) {
+      if (i & 1) dp = mfma32(op[i], vreg[i >> 1], dp);
+      else s = mfma32(op[i], kreg[i >> 1], s);
+    }
+  };
+
+  // Vector work for logit e of the current block (statistics l, d of its query row).
+  auto b_element = [&](auto masked, int e, float l, float d, int sub_lo, float* pr, float* ds) __attribute__((always_inline)) {
+    float se = s[e];
+    if (decltype(masked)::value) {
+      const int qidx = sub_lo + acc_row(e, g);
+      if (qidx < lo_k || qidx >= hi_k) se = -INFINITY;
+    }
+    pr[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(se, p.scale_log2, -l));
+    ds[e] = pr[e] * (dp[e] - d);
+  };
+
+  // Stage B(cur) interleaved with stage A(next) when kNext, else B alone.
+  //   nsub: LDS offset of the next block's rows relative to `rm`;
+  //   csub_stat: offset of the current block's statistics relative to `st`.
+  auto stage_ab = [&](auto has_next, auto masked, uint32_t nsub, uint32_t csub_stat, int sub_lo) __attribute__((always_inline)) {
+    constexpr bool kNext = decltype(has_next)::value;
+    constexpr int kAhead = 3;                     // LDS reads run this many MFMAs ahead
+    f32x16 sn, dpn;
+    bf16x8 op[kNA];
+    f32x4 l4[4], d4[4];
+    float pr[16], ds[16];
+#pragma unroll
+    for (int vq = 0; vq < 4; ++vq) {
+      l4[vq] = *reinterpret_cast<const AERIS_LDS f32x4*>(st + csub_stat + vq * 32);
+      d4[vq] = *reinterpret_cast<const AERIS_LDS f32x4*>(st + csub_stat + vq * 32 + kStream * 4);
+    }
+    if (kNext) {
+#pragma unroll
+      for (int i = 0; i < kAhead; ++i) op[i] = a_operand(i, nsub);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { sn[i] = 0.f; dpn[i] = 0.f; }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // 16 slots: slot e carries logit e, and MFMAs e*kNA/16 .. of stage A
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      if (kNext) {
+#pragma unroll
+        for (int i = e * kNA / 16; i < (e + 1) * kNA / 16; ++i) {
+          if (i + kAhead < kNA) op[i + kAhead] = a_operand(i + kAhead, nsub);
+          if (i & 1) dpn = mfma32(op[i], vreg[i >> 1], dpn);
+          else sn = mfma32(op[i], kreg[i >> 1], sn);
+        }
+      }
+      b_element(masked, e, l4[e >> 2][e & 3], d4[e >> 2][e & 3], sub_lo, pr, ds);
+      if (e & 1) {
+        const int c = e >> 3, w = (e >> 1) & 3;
+        pb[c].u[w] = pack_bf16(pr[e - 1], pr[e]);
+        dsb[c].u[w] = pack_bf16(ds[e - 1], ds[e]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (kNext) {
+      s = sn;
+      dp = dpn;
+    }
+  };
+
+  // Stage C: the 16 accumulating products of the current block.
+  auto stage_c = [&](uint32_t sub) __attribute__((always_inline)) {
+    constexpr int kAhead = 3;
+    bf16x8 op[kNC];
+#pragma unroll
+    for (int i = 0; i < kAhead; ++i) op[i] = c_operand(i, sub);
+#pragma unroll
+    for (int i = 0; i < kNC; ++i) {
+      if (i + kAhead < kNC) op[i + kAhead] = c_operand(i + kAhead, sub);
+      const int cb = i >> 2, c = (i >> 1) & 1;
+      if (i & 1) dkacc[cb] = mfma32(op[i], dsb[c].h, dkacc[cb]);
+      else dvacc[cb] = mfma32(op[i], pb[c].h, dvacc[cb]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  auto run_ab = [&](bool has_next, uint32_t nsub, uint32_t csub_stat, int sub_lo) __attribute__((always_inline)) {
+    const bool mf = rg.mask_free(sub_lo);
+    if (has_next) {
+      if (mf) stage_ab(std::true_type{}, std::false_type{}, nsub, csub_stat, sub_lo);
+      else stage_ab(std::true_type{}, std::true_type{}, nsub, csub_stat, sub_lo);
+    } else {
+      if (mf) stage_ab(std::false_type{}, std::false_type{}, nsub, csub_stat, sub_lo);
+      else stage_ab(std::false_type{}, std::true_type{}, nsub, csub_stat, sub_lo);
+    }
+  };
+
+  // ---- prologue: first tile visible, second one requested, logits of block 0 ----
+  wait_async_loads();
+  __syncthreads();
+  if (qt_begin + 1 < qt_end) fill(tiles + kBuf, (qt_begin + 1) * kStream);
+  if (rg.wave_active) stage_a(0);
+  int a_buf = 0, c_buf = 0;   // buffer index `rm` / `tr`,`st` point into
+
+  AERIS_TICK_DECL
+  for (int qt = qt_begin; qt < qt_end; ++qt) {
+    const bool more = qt + 1 < qt_end;
+    AERIS_TICK(7)
+    // first half: A(tile qt, block 1) with B(tile qt, block 0); then C(block 0)
+    if (rg.wave_active) {
+      run_ab(true, Tl::kSubBytes, 0, qt * kStream);
+      AERIS_TICK(0)
+      stage_c(0);
+      AERIS_TICK(1)
+    }
+    // tile qt+1 must be visible before stage A touches it; this barrier also
+    // retires every reader of tile qt-1, whose buffer the new fill reuses
+    if (more) {
+      wait_async_loads();
+      AERIS_TICK(5)
+      __syncthreads();
+      AERIS_TICK(6)
+      if (qt + 2 < qt_end) {
+        const int f_buf = a_buf == 0 ? 2 : a_buf - 1;   // (a_buf + 2) % 3
+        fill(tiles + f_buf * kBuf, (qt + 2) * kStream);
+      }
+      const uint32_t step = a_buf == 2 ? (uint32_t)(-2 * (int)kBuf) : kBuf;
+      a_buf = a_buf == 2 ? 0 : a_buf + 1;
+#pragma unroll
+      for (int kk = 0; kk < kNK; ++kk) la.rm[kk] += step;
+    }
+    AERIS_TICK(2)
+    // second half: A(tile qt+1, block 0) with B(tile qt, block 1); then C(block 1)
+    if (rg.wave_active) {
+      run_ab(more, 0, 32 * 4, qt * kStream + 32);
+      AERIS_TICK(3)
+      stage_c(Tl::kSubBytes);
+      AERIS_TICK(4)
+    }
+    {
+      const uint32_t step = c_buf == 2 ? (uint32_t)(-2 * (int)kBuf) : kBuf;
+      c_buf = c_buf == 2 ? 0 : c_buf + 1;
+#pragma unroll
+      for (int cb = 0; cb < D / 32; ++cb) {
+        la.tr[cb][0] += step;
+        la.tr[cb][1] += step;
+      }
+      st += step;
+    }
+  }
+  AERIS_TICK_FLUSH
+
+  if (!rg.valid) return;
+  OutT* dkrow = dk + qkv_base + (long long)k_grid * p.qkv_tok;
+  OutT* dvrow = dv + qkv_base + (long long)k_grid * p.qkv_tok;
+#pragma unroll
+  for (int cb = 0; cb < D / 32; ++cb)
+#pragma unroll
+    for (int vq = 0; vq < 4; ++vq) {
+      const int ch = cb * 32 + 8 * vq + 4 * g;
+      store4(dkrow + ch, dkacc[cb][4 * vq] * p.scale, dkacc[cb][4 * vq + 1] * p.scale,
+             dkacc[cb][4 * vq + 2] * p.scale, dkacc[cb][4 * vq + 3] * p.scale);
+      store4(dvrow + ch, dvacc[cb][4 * vq], dvacc[cb][4 * vq + 1], dvacc[cb][4 * vq + 2],
+             dvacc[cb][4 * vq + 3]);
+    }
+}
+
+template <int D, typename OutT>
+static int launch_t(const KParams& kp, const void* q, const void* k, const void* v,
+                    const void* d_o, const float* delta, const float* lse2, void* dk, void* dv,
+                    hipStream_t stream) {
+  const size_t smem = dkdv_pipe_smem_bytes<D>(kp.T);
+  auto kern = winattn_dkdv_pipe_kernel<D, OutT>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+    return -1;
+  hipLaunchKernelGGL(kern, dim3(grid_blocks(kp)), dim3(kThreads), smem, stream, kp,
+                     static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
+                     static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(d_o), delta, lse2,
+                     static_cast<OutT*>(dk), static_cast<OutT*>(dv));
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int launch_dkdv_pipe128(const KParams& kp, bool out_f32, const void* q, const void* k,
+                        const void* v, const void* d_o, const float* delta, const float* lse2,
+                        void* dk, void* dv, hipStream_t stream) {
+  return out_f32 ? launch_t<128, float>(kp, q, k, v, d_o, delta, lse2, dk, dv, stream)
+                 : launch_t<128, bf16_t>(kp, q, k, v, d_o, delta, lse2, dk, dv, stream);
+}
+
+}  // namespace aeris
+
+#ifdef AERIS_STAGE_TIMING
+extern "C" int aeris_debug_read(unsigned long long* out) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(aeris_stage_ticks),
+                                  16 * sizeof(unsigned long long));
+}
+#endif

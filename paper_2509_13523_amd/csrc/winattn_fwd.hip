@@ -83,7 +83,7 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
 
   // One 32-key block at compile-time LDS offset kOff from buffer 0 / sub-block 0:
   // every operand address is a per-lane register plus an immediate.
-  auto sub_block = [&](auto off, int sub_lo) {
+  auto sub_block = [&](auto off, int sub_lo) __attribute__((always_inline)) {
     constexpr uint32_t kOff = decltype(off)::value;
     if (rg.skip(sub_lo)) return;   // wave-uniform
     // ---- operand reads first, products after: LDS latency hides behind the MFMA
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
   // One streamed tile held in buffer kP (compile time); the next one flies into
   // the other buffer during the math.  One barrier per tile: it publishes tile
   // kt and retires the readers of tile kt-1, whose buffer the new fill reuses.
-  auto tile_step = [&](auto parity, int kt) {
+  auto tile_step = [&](auto parity, int kt) __attribute__((always_inline)) {
     constexpr uint32_t kP = decltype(parity)::value;
     wait_async_loads();
     __syncthreads();

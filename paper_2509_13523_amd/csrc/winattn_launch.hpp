@@ -13,6 +13,12 @@ int launch_bwd(const KParams& kp, int head_dim, bool out_f32, const void* q, con
                const void* v, const void* o, const float* lse, const void* d_o, void* dq,
                void* dk, void* dv, float* workspace, hipStream_t stream, unsigned stages);
 
+// Software-pipelined dK/dV kernel for head_dim 128 (same contract as the dK/dV stage of
+// launch_bwd; delta and lse2 are the two workspace vectors).
+int launch_dkdv_pipe128(const KParams& kp, bool out_f32, const void* q, const void* k,
+                        const void* v, const void* d_o, const float* delta, const float* lse2,
+                        void* dk, void* dv, hipStream_t stream);
+
 // Bytes of device workspace launch_bwd needs for these parameters.
 size_t bwd_workspace_bytes(const KParams& kp);
 
