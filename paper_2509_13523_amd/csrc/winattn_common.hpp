@@ -293,6 +293,23 @@ struct Tile {
         src[i] = reinterpret_cast<const char*>(origin) + c * 16;
       }
     }
+    // Two-phase fill: prepare() reads the table entries of tile t0 into registers
+    // (call it well ahead, so the LDS latency is not exposed), issue_one()/issue()
+    // launch the copies.  Between the two calls the registers g[] stay live.
+    uint32_t g[kFillPerWave];
+    __device__ __forceinline__ void prepare(int t0) {
+      const uint32_t row0 = tab + t0 * 4;
+#pragma unroll
+      for (int i = 0; i < kFillPerWave; ++i)
+        g[i] = *reinterpret_cast<const AERIS_LDS uint32_t*>(row0 + i * kRowsPerInst * 4);
+    }
+    __device__ __forceinline__ void issue_one(int i, uint32_t tile) const {
+      async_copy16(src[i] + (unsigned long long)g[i] * stride_bytes, tile + dst + i * 1024);
+    }
+    __device__ __forceinline__ void issue(uint32_t tile) const {
+#pragma unroll
+      for (int i = 0; i < kFillPerWave; ++i) issue_one(i, tile);
+    }
     // tile: LDS byte address (wave-uniform); t0: first token (multiple of kStream).
     __device__ __forceinline__ void fill(uint32_t tile, int t0) const {
       const uint32_t row0 = tab + t0 * 4;

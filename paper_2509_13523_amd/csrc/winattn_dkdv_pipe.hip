@@ -215,8 +215,18 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
     }
   };
 
-  // Stage C: the 16 accumulating products of the current block.
-  auto stage_c = [&](uint32_t sub) __attribute__((always_inline)) {
+  // piece i (0 .. 2*kFillPerWave) of a tile fill whose table entries were prepared
+  // earlier: Q rows, dO rows, statistics
+  auto fill_piece = [&](int i, uint32_t buf, int t0) __attribute__((always_inline)) {
+    if (i < Tl::kFillPerWave) qfill.issue_one(i, buf);
+    else if (i < 2 * Tl::kFillPerWave) dofill.issue_one(i - Tl::kFillPerWave, buf + Tl::kBytes);
+    else if (wave < 2) async_copy4(stat_src + t0, buf + kStat + wave * (kStream * 4));
+  };
+
+  // Stage C: the 16 accumulating products of the current block.  When do_fill
+  // (wave-uniform), the pieces of a tile fill are dropped between the MFMAs one at a
+  // time: issued as a burst they stall the wave until the memory pipeline drains.
+  auto stage_c = [&](uint32_t sub, bool do_fill, uint32_t fill_buf, int fill_t0) __attribute__((always_inline)) {
     constexpr int kAhead = 3;
     bf16x8 op[kNC];
 #pragma unroll
@@ -227,6 +237,7 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
       const int cb = i >> 2, c = (i >> 1) & 1;
       if (i & 1) dkacc[cb] = mfma32(op[i], dsb[c].h, dkacc[cb]);
       else dvacc[cb] = mfma32(op[i], pb[c].h, dvacc[cb]);
+      if (i <= 2 * Tl::kFillPerWave && do_fill) fill_piece(i, fill_buf, fill_t0);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -257,32 +268,38 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
     if (rg.wave_active) {
       run_ab(true, Tl::kSubBytes, 0, qt * kStream);
       AERIS_TICK(0)
-      stage_c(0);
+      stage_c(0, false, 0, 0);
       AERIS_TICK(1)
     }
     // tile qt+1 must be visible before stage A touches it; this barrier also
     // retires every reader of tile qt-1, whose buffer the new fill reuses
+    const bool do_fill = qt + 2 < qt_end;               // tile qt+2 goes to buffer (a_buf + 2) % 3
+    const uint32_t fill_buf = tiles + (a_buf == 0 ? 2 : a_buf - 1) * kBuf;
+    const int fill_t0 = (qt + 2) * kStream;
     if (more) {
       wait_async_loads();
       AERIS_TICK(5)
       __syncthreads();
       AERIS_TICK(6)
-      if (qt + 2 < qt_end) {
-        const int f_buf = a_buf == 0 ? 2 : a_buf - 1;   // (a_buf + 2) % 3
-        fill(tiles + f_buf * kBuf, (qt + 2) * kStream);
-      }
       const uint32_t step = a_buf == 2 ? (uint32_t)(-2 * (int)kBuf) : kBuf;
       a_buf = a_buf == 2 ? 0 : a_buf + 1;
 #pragma unroll
       for (int kk = 0; kk < kNK; ++kk) la.rm[kk] += step;
+    }
+    if (do_fill) {            // table entries of tile qt+2: read now, used a whole stage later
+      qfill.prepare(fill_t0);
+      dofill.prepare(fill_t0);
     }
     AERIS_TICK(2)
     // second half: A(tile qt+1, block 0) with B(tile qt, block 1); then C(block 1)
     if (rg.wave_active) {
       run_ab(more, 0, 32 * 4, qt * kStream + 32);
       AERIS_TICK(3)
-      stage_c(Tl::kSubBytes);
+      stage_c(Tl::kSubBytes, do_fill, fill_buf, fill_t0);   // after the barrier: buffer is free
       AERIS_TICK(4)
+    } else if (do_fill) {        // waves without real keys still move their share of the tile
+#pragma unroll
+      for (int i = 0; i <= 2 * Tl::kFillPerWave; ++i) fill_piece(i, fill_buf, fill_t0);
     }
     {
       const uint32_t step = c_buf == 2 ? (uint32_t)(-2 * (int)kBuf) : kBuf;
