@@ -127,11 +127,15 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
 
   const int kt_begin = rg.wg_lo / kStream;
   const int kt_end = (rg.wg_hi + kStream - 1) / kStream;
+  typename Tl::Rows rows;
   typename Tl::Filler kfill, vfill;
-  kfill.init(k + qkv_base, p.qkv_tok, table, wave, lane);
-  vfill.init(v + qkv_base, p.qkv_tok, table, wave, lane);
-  kfill.fill(tiles, kt_begin * kStream);
-  vfill.fill(tiles + Tl::kBytes, kt_begin * kStream);
+  rows.init(table, wave, lane);
+  kfill.init(k + qkv_base, p.qkv_tok, wave, lane);
+  vfill.init(v + qkv_base, p.qkv_tok, wave, lane);
+  rows.prepare(kt_begin * kStream);
+  kfill.issue(tiles, rows);
+  vfill.issue(tiles + Tl::kBytes, rows);
+  if (kt_begin + 1 < kt_end) rows.prepare((kt_begin + 1) * kStream);
 
   bf16x8 qreg[D / 16], doreg[D / 16];
   {
@@ -213,9 +217,10 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
     constexpr uint32_t kP = decltype(parity)::value;
     wait_async_loads();
     __syncthreads();
-    if (kt + 1 < kt_end) {
-      kfill.fill(tiles + (1 - kP) * kBuf, (kt + 1) * kStream);
-      vfill.fill(tiles + (1 - kP) * kBuf + Tl::kBytes, (kt + 1) * kStream);
+    if (kt + 1 < kt_end) {     // table entries were read one tile ago
+      kfill.issue(tiles + (1 - kP) * kBuf, rows);
+      vfill.issue(tiles + (1 - kP) * kBuf + Tl::kBytes, rows);
+      if (kt + 2 < kt_end) rows.prepare((kt + 2) * kStream);
     }
     if (!rg.wave_active) return;
     sub_block(Const<kP * kBuf>{}, kt * kStream);
@@ -281,19 +286,24 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 1 : 2) void winattn_dkdv_kerne
   const int lo_k = rg.lo, hi_k = rg.hi;
 
   // one streamed tile: Q, dO (all waves), LSE*log2e (wave 0), delta (wave 1)
+  typename Tl::Rows rows;
   typename Tl::Filler qfill, dofill;
-  qfill.init(q + qkv_base, p.qkv_tok, table, wave, lane);
-  dofill.init(d_o + o_base, p.o_tok, table, wave, lane);
+  rows.init(table, wave, lane);
+  qfill.init(q + qkv_base, p.qkv_tok, wave, lane);
+  dofill.init(d_o + o_base, p.o_tok, wave, lane);
   const float* stat_src = (wave == 0 ? lse2v : delta) + (long long)pair * p.T + lane;
+  // launches the fill of tile t0, whose table entries `rows` holds
   auto fill = [&](uint32_t buf, int t0) __attribute__((always_inline)) {
-    qfill.fill(buf, t0);
-    dofill.fill(buf + Tl::kBytes, t0);
+    qfill.issue(buf, rows);
+    dofill.issue(buf + Tl::kBytes, rows);
     if (wave < 2) async_copy4(stat_src + t0, buf + kStat + wave * (kStream * 4));
   };
 
   const int qt_begin = rg.wg_lo / kStream;
   const int qt_end = (rg.wg_hi + kStream - 1) / kStream;
+  rows.prepare(qt_begin * kStream);
   fill(tiles, qt_begin * kStream);
+  if (qt_begin + 1 < qt_end) rows.prepare((qt_begin + 1) * kStream);
 
   bf16x8 kreg[D / 16], vreg[D / 16];
   {
@@ -393,7 +403,10 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 1 : 2) void winattn_dkdv_kerne
     constexpr uint32_t kP = decltype(parity)::value;
     wait_async_loads();
     __syncthreads();
-    if (qt + 1 < qt_end) fill(tiles + (1 - kP) * kBuf, (qt + 1) * kStream);
+    if (qt + 1 < qt_end) {
+      fill(tiles + (1 - kP) * kBuf, (qt + 1) * kStream);
+      if (qt + 2 < qt_end) rows.prepare((qt + 2) * kStream);
+    }
     if (!rg.wave_active) return;
     sub_block(Const<kP * kBuf>{}, Const<kP * kBuf>{}, qt * kStream);
     sub_block(Const<kP * kBuf + Tl::kSubBytes>{}, Const<kP * kBuf + 32 * 4>{}, qt * kStream + 32);

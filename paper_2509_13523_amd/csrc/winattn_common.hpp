@@ -272,20 +272,37 @@ struct Tile {
   }
 
   // Asynchronous tile fill.  Per lane and wave instruction i, the source is
-  //   base + table[t0 + row_i] * stride_bytes + chunk_i * 16
+  //   origin + table[t0 + row_i] * stride_bytes + chunk_i * 16
   // (one LDS table read and one 64-bit multiply-add per 16 bytes moved).
+  // Two phases, so the table read's latency is never exposed and the copies can be
+  // spread over a compute phase (a burst of them stalls the issuing wave until the
+  // memory pipeline drains): Rows::prepare() reads the table entries of a tile into
+  // registers; Filler::issue_one()/issue() launch the copies of one tensor.  Tensors
+  // streamed together (K and V, or Q and dO) share one Rows.
+  static constexpr int kRowsPerInst = 64 / NC;
+  struct Rows {
+    uint32_t tab;                    // LDS byte address of table[row of instruction 0]
+    uint32_t g[kFillPerWave];        // grid index of the lane's row in each instruction
+    __device__ __forceinline__ void init(uint32_t table_lds, int wave, int lane) {
+      tab = table_lds + (wave * kFillPerWave * kRowsPerInst + lane / NC) * 4;
+    }
+    // t0: first token of the tile (multiple of kStream)
+    __device__ __forceinline__ void prepare(int t0) {
+      const uint32_t row0 = tab + t0 * 4;
+#pragma unroll
+      for (int i = 0; i < kFillPerWave; ++i)
+        g[i] = *reinterpret_cast<const AERIS_LDS uint32_t*>(row0 + i * kRowsPerInst * 4);
+    }
+  };
   struct Filler {
     const char* src[kFillPerWave];   // tensor origin of this (batch, head) + lane's chunk
-    uint32_t tab;                    // LDS byte address of table[row of instruction 0]
     uint32_t dst;                    // byte offset of this wave's first instruction in a tile
     uint32_t stride_bytes;
-    static constexpr int kRowsPerInst = 64 / NC;
 
-    __device__ __forceinline__ void init(const bf16_t* origin, long long tok_stride,
-                                         uint32_t table_lds, int wave, int lane) {
+    __device__ __forceinline__ void init(const bf16_t* origin, long long tok_stride, int wave,
+                                         int lane) {
       stride_bytes = (uint32_t)(tok_stride * 2);
       dst = wave * kFillPerWave * 1024;
-      tab = table_lds + (wave * kFillPerWave * kRowsPerInst + lane / NC) * 4;
 #pragma unroll
       for (int i = 0; i < kFillPerWave; ++i) {
         const int r = (wave * kFillPerWave + i) * kRowsPerInst + lane / NC;
@@ -293,32 +310,13 @@ struct Tile {
         src[i] = reinterpret_cast<const char*>(origin) + c * 16;
       }
     }
-    // Two-phase fill: prepare() reads the table entries of tile t0 into registers
-    // (call it well ahead, so the LDS latency is not exposed), issue_one()/issue()
-    // launch the copies.  Between the two calls the registers g[] stay live.
-    uint32_t g[kFillPerWave];
-    __device__ __forceinline__ void prepare(int t0) {
-      const uint32_t row0 = tab + t0 * 4;
-#pragma unroll
-      for (int i = 0; i < kFillPerWave; ++i)
-        g[i] = *reinterpret_cast<const AERIS_LDS uint32_t*>(row0 + i * kRowsPerInst * 4);
+    // tile: LDS byte address (wave-uniform)
+    __device__ __forceinline__ void issue_one(int i, uint32_t tile, const Rows& rows) const {
+      async_copy16(src[i] + (unsigned long long)rows.g[i] * stride_bytes, tile + dst + i * 1024);
     }
-    __device__ __forceinline__ void issue_one(int i, uint32_t tile) const {
-      async_copy16(src[i] + (unsigned long long)g[i] * stride_bytes, tile + dst + i * 1024);
-    }
-    __device__ __forceinline__ void issue(uint32_t tile) const {
+    __device__ __forceinline__ void issue(uint32_t tile, const Rows& rows) const {
 #pragma unroll
-      for (int i = 0; i < kFillPerWave; ++i) issue_one(i, tile);
-    }
-    // tile: LDS byte address (wave-uniform); t0: first token (multiple of kStream).
-    __device__ __forceinline__ void fill(uint32_t tile, int t0) const {
-      const uint32_t row0 = tab + t0 * 4;
-#pragma unroll
-      for (int i = 0; i < kFillPerWave; ++i) {
-        const uint32_t g =
-            *reinterpret_cast<const AERIS_LDS uint32_t*>(row0 + i * kRowsPerInst * 4);
-        async_copy16(src[i] + (unsigned long long)g * stride_bytes, tile + dst + i * 1024);
-      }
+      for (int i = 0; i < kFillPerWave; ++i) issue_one(i, tile, rows);
     }
   };
 

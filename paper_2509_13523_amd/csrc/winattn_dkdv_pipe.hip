@@ -84,18 +84,22 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
   const int k_grid = tok_grid[rg.tok];
   const int lo_k = rg.lo, hi_k = rg.hi;
 
+  typename Tl::Rows rows;
   typename Tl::Filler qfill, dofill;
-  qfill.init(q + qkv_base, p.qkv_tok, table, wave, lane);
-  dofill.init(d_o + o_base, p.o_tok, table, wave, lane);
+  rows.init(table, wave, lane);
+  qfill.init(q + qkv_base, p.qkv_tok, wave, lane);
+  dofill.init(d_o + o_base, p.o_tok, wave, lane);
   const float* stat_src = (wave == 0 ? lse2v : delta) + (long long)pair * p.T + lane;
+  // launches the fill of tile t0, whose table entries `rows` holds
   auto fill = [&](uint32_t buf, int t0) __attribute__((always_inline)) {
-    qfill.fill(buf, t0);
-    dofill.fill(buf + Tl::kBytes, t0);
+    qfill.issue(buf, rows);
+    dofill.issue(buf + Tl::kBytes, rows);
     if (wave < 2) async_copy4(stat_src + t0, buf + kStat + wave * (kStream * 4));
   };
 
   const int qt_begin = rg.wg_lo / kStream;
   const int qt_end = (rg.wg_hi + kStream - 1) / kStream;
+  rows.prepare(qt_begin * kStream);
   fill(tiles, qt_begin * kStream);
 
   bf16x8 kreg[kNK], vreg[kNK];
@@ -218,8 +222,8 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
   // piece i (0 .. 2*kFillPerWave) of a tile fill whose table entries were prepared
   // earlier: Q rows, dO rows, statistics
   auto fill_piece = [&](int i, uint32_t buf, int t0) __attribute__((always_inline)) {
-    if (i < Tl::kFillPerWave) qfill.issue_one(i, buf);
-    else if (i < 2 * Tl::kFillPerWave) dofill.issue_one(i - Tl::kFillPerWave, buf + Tl::kBytes);
+    if (i < Tl::kFillPerWave) qfill.issue_one(i, buf, rows);
+    else if (i < 2 * Tl::kFillPerWave) dofill.issue_one(i - Tl::kFillPerWave, buf + Tl::kBytes, rows);
     else if (wave < 2) async_copy4(stat_src + t0, buf + kStat + wave * (kStream * 4));
   };
 
@@ -256,7 +260,10 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
   // ---- prologue: first tile visible, second one requested, logits of block 0 ----
   wait_async_loads();
   __syncthreads();
-  if (qt_begin + 1 < qt_end) fill(tiles + kBuf, (qt_begin + 1) * kStream);
+  if (qt_begin + 1 < qt_end) {
+    rows.prepare((qt_begin + 1) * kStream);
+    fill(tiles + kBuf, (qt_begin + 1) * kStream);
+  }
   if (rg.wave_active) stage_a(0);
   int a_buf = 0, c_buf = 0;   // buffer index `rm` / `tr`,`st` point into
 
@@ -286,10 +293,7 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
 #pragma unroll
       for (int kk = 0; kk < kNK; ++kk) la.rm[kk] += step;
     }
-    if (do_fill) {            // table entries of tile qt+2: read now, used a whole stage later
-      qfill.prepare(fill_t0);
-      dofill.prepare(fill_t0);
-    }
+    if (do_fill) rows.prepare(fill_t0);   // table entries of tile qt+2: used a whole stage later
     AERIS_TICK(2)
     // second half: A(tile qt+1, block 0) with B(tile qt, block 1); then C(block 1)
     if (rg.wave_active) {

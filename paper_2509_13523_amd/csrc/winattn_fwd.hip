@@ -55,11 +55,15 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
 
   const int kt_begin = rg.wg_lo / kStream;
   const int kt_end = (rg.wg_hi + kStream - 1) / kStream;
+  typename Tl::Rows rows;
   typename Tl::Filler kfill, vfill;
-  kfill.init(k + qkv_base, p.qkv_tok, table, wave, lane);
-  vfill.init(v + qkv_base, p.qkv_tok, table, wave, lane);
-  kfill.fill(tiles, kt_begin * kStream);
-  vfill.fill(tiles + Tl::kBytes, kt_begin * kStream);
+  rows.init(table, wave, lane);
+  kfill.init(k + qkv_base, p.qkv_tok, wave, lane);
+  vfill.init(v + qkv_base, p.qkv_tok, wave, lane);
+  rows.prepare(kt_begin * kStream);
+  kfill.issue(tiles, rows);
+  vfill.issue(tiles + Tl::kBytes, rows);
+  if (kt_begin + 1 < kt_end) rows.prepare((kt_begin + 1) * kStream);
 
   bf16x8 qreg[D / 16];
   {
@@ -156,9 +160,10 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
     constexpr uint32_t kP = decltype(parity)::value;
     wait_async_loads();
     __syncthreads();
-    if (kt + 1 < kt_end) {
-      kfill.fill(tiles + (1 - kP) * kBuf, (kt + 1) * kStream);
-      vfill.fill(tiles + (1 - kP) * kBuf + Tl::kBytes, (kt + 1) * kStream);
+    if (kt + 1 < kt_end) {     // table entries were read one tile ago
+      kfill.issue(tiles + (1 - kP) * kBuf, rows);
+      vfill.issue(tiles + (1 - kP) * kBuf + Tl::kBytes, rows);
+      if (kt + 2 < kt_end) rows.prepare((kt + 2) * kStream);
     }
     if (!rg.wave_active) return;
     sub_block(Const<kP * kBuf>{}, kt * kStream);
