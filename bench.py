@@ -36,9 +36,10 @@ WORKLOADS = {
                name="720x1440 grid, 16 heads x 64, 60x60 windows, shift 30, forward only"),
 }
 
-# HBM traffic of the dominant kernel per launch, bytes, from rocprofv3 --pmc runs
-# (FETCH_SIZE and WRITE_SIZE scaled by a copy kernel of known size); see profiles/.
-MEASURED_TRAFFIC = {}
+# HBM traffic per launch, bytes, from two rocprofv3 --pmc runs of this file (FETCH_SIZE, then
+# WRITE_SIZE, each scaled by what the same counter reads for the --calibrate-copy kernels:
+# factors 2.000 and 1.000); profiles/c5_kernels_and_counters.txt has the commands and numbers.
+MEASURED_TRAFFIC = {("c5", "fwd"): 78.0e9, ("c5", "dq"): 88.7e9, ("c5", "dkdv"): 112.3e9}
 
 
 def unmasked_pairs(H, W, win, shift, mask):
@@ -144,7 +145,8 @@ def main():
     dom = max((k for k in kern if kernel_flops[k]), key=lambda k: kern[k]["avg_ms"] * len(events[k]))
     dom_flops = kernel_flops[dom] * d * sum(U.values()) / len(U)
     achieved = dom_flops / (kern[dom]["avg_ms"] * 1e-3) / 1e12
-    roofline = {"kernel": "winattn_%s_kernel" % dom, "bound": "mfma", "achieved": round(achieved, 2),
+    kname = "winattn_dkdv_pipe_kernel" if (dom == "dkdv" and d == 128) else "winattn_%s_kernel" % dom
+    roofline = {"kernel": kname, "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                 "traffic": MEASURED_TRAFFIC.get((args.workload, dom))}
