@@ -31,6 +31,13 @@ WORKLOADS = {
     "c4": dict(shape=(1, 120, 1440, 24, 128), win=(60, 60), layers=[(30, 30)], mask=2,
                kind="blend", sigmas=None, bwd=True, seed=4000,
                name="48 windows 60x60 (2x24 band), 24 heads x 128, shift 30, SWIN mask"),
+    # small parity-test configurations (HBM/latency-bound: judge them on GB/s)
+    "c1": dict(shape=(1, 64, 128, 4, 32), win=(8, 8), layers=[(0, 0), (4, 4)], mask=2,
+               kind="normal", sigmas=None, bwd=False, seed=1000,
+               name="64x128 grid, 4 heads x 32, 8x8 windows, shift 0/4, forward only"),
+    "c2": dict(shape=(1, 180, 360, 8, 64), win=(12, 12), layers=[(0, 0), (6, 6)], mask=2,
+               kind="normal", sigmas=None, bwd=True, seed=2000,
+               name="180x360 grid, 8 heads x 64, 12x12 windows, shift 0/6"),
     "c3": dict(shape=(1, 720, 1440, 16, 64), win=(60, 60), layers=[(30, 30)], mask=2,
                kind="normal", sigmas=None, bwd=False, seed=3000,
                name="720x1440 grid, 16 heads x 64, 60x60 windows, shift 30, forward only"),
@@ -162,6 +169,11 @@ def main():
                       "layers_per_step": len(wl["layers"]),
                       "model_tflop_per_step": round(model_flops / 1e12, 2)},
            "kernels": kern, "roofline": roofline}
+    # algorithmic HBM bytes per step: fwd reads Q,K,V and writes O, LSE; bwd reads Q,K,V,O,dO
+    # twice over its three kernels (O,dO; Q,K,V,dO; Q,K,V,dO) and writes dQ,dK,dV
+    tensor = 2.0 * Bn * H * W * nh * d
+    step_bytes = len(wl["layers"]) * ((4 + (13 if wl["bwd"] else 0)) * tensor)
+    out["algorithmic_gbs"] = round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1)
 
     if args.calibrate_copy:
         a = torch.zeros(1 << 28, dtype=torch.float32, device=dev)

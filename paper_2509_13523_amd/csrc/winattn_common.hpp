@@ -159,6 +159,14 @@ struct Ranges {
       win.range(wave_t0, w_lo, hi_min);
       win.range(last < T ? last : T - 1, lo_max, w_hi);
     }
+    // wave-uniform by construction: keep them in scalar registers, so that skip()
+    // and mask_free() become scalar branches instead of predicated vector code
+    w_lo = __builtin_amdgcn_readfirstlane(w_lo);
+    w_hi = __builtin_amdgcn_readfirstlane(w_hi);
+    lo_max = __builtin_amdgcn_readfirstlane(lo_max);
+    hi_min = __builtin_amdgcn_readfirstlane(hi_min);
+    wg_lo = __builtin_amdgcn_readfirstlane(wg_lo);
+    wg_hi = __builtin_amdgcn_readfirstlane(wg_hi);
   }
   // Block [s, s+32) of streamed tokens: does this wave need it, and masked?
   __device__ __forceinline__ bool skip(int s) const { return s + 32 <= w_lo || s >= w_hi; }
@@ -231,14 +239,31 @@ __device__ __forceinline__ uint32_t lds_address(const void* generic) {
 // that the compiler does not serialise later LDS reads of OTHER buffers behind
 // it; completion is awaited explicitly with wait_async_loads() + a barrier.
 __device__ __forceinline__ void async_copy16(const void* src, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :
                : "v"(src), "s"(__builtin_amdgcn_readfirstlane(lds_base))
                : "memory");
 }
+// The same, executed only if `enable` (wave-uniform) is non-zero.  The scalar branch
+// sits inside the statement, so a hand-placed schedule keeps the copy at a fixed
+// place without the compiler splitting the surrounding code into blocks.
+__device__ __forceinline__ void async_copy16_if(const void* src, uint32_t lds_base,
+                                                uint32_t enable) {
+  asm volatile(
+      "s_cmp_eq_u32 %2, 0\n\t"
+      "s_cbranch_scc1 1f\n\t"
+      "s_mov_b32 m0, %1\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, off\n"
+      "1:"
+      :
+      : "v"(src), "s"(__builtin_amdgcn_readfirstlane(lds_base)),
+        "s"(__builtin_amdgcn_readfirstlane(enable))
+      : "memory", "scc");
+}
 // 4 bytes per lane: lane l's dword lands at lds_base + 4*l.
 __device__ __forceinline__ void async_copy4(const void* src, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off"
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
                :
                : "v"(src), "s"(__builtin_amdgcn_readfirstlane(lds_base))
                : "memory");
@@ -252,6 +277,32 @@ template <typename V>
 __device__ __forceinline__ void settle(V& v) {
   asm volatile("" : "+v"(v));
 }
+
+// Nothing is scheduled across this point: pins a hand-made interleaving of
+// products, operand reads and copies.
+__device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
+
+// Optional stage timing (development aid, off by default): -DAERIS_STAGE_TIMING makes one
+// wave of one workgroup accumulate the 100 MHz wall clock per schedule stage into a
+// __device__ array, which a harness reads back with hipMemcpyFromSymbol.
+#ifdef AERIS_STAGE_TIMING
+#define AERIS_TICK_DECL                                                              \
+  const bool tick_on = blockIdx.x == 8 * 40 + 3 && threadIdx.x == 0;                 \
+  unsigned long long tick_last = wall_clock64(), tick_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#define AERIS_TICK(i)                                 \
+  if (tick_on) {                                      \
+    const unsigned long long t = wall_clock64();      \
+    tick_acc[i] += t - tick_last;                     \
+    tick_last = t;                                    \
+  }
+#define AERIS_TICK_FLUSH(array) \
+  if (tick_on)                  \
+    for (int i = 0; i < 8; ++i) array[i] = tick_acc[i];
+#else
+#define AERIS_TICK_DECL
+#define AERIS_TICK(i)
+#define AERIS_TICK_FLUSH(array)
+#endif
 
 template <int D>
 struct Tile {
@@ -271,52 +322,66 @@ struct Tile {
     return (r * NC + (c ^ swz(r))) * 16;
   }
 
-  // Asynchronous tile fill.  Per lane and wave instruction i, the source is
-  //   origin + table[t0 + row_i] * stride_bytes + chunk_i * 16
-  // (one LDS table read and one 64-bit multiply-add per 16 bytes moved).
+  // Asynchronous tile fill.  A wave instruction moves 64 chunks = kRowsPerInst token
+  // rows.  Instruction i of wave w covers rows
+  //   i * kRowStep + w * kRowsPerInst + lane / NC,      kRowStep = kRowsPerInst * kWaves,
+  // and because swz() has period 16 (which divides kRowStep) the lane's source chunk is
+  // the same in every instruction: per 16 bytes moved the source is
+  //   src + table[t0 + row_i] * stride_bytes
+  // (one LDS table read and one 64-bit multiply-add), with ONE pointer per tensor.
   // Two phases, so the table read's latency is never exposed and the copies can be
   // spread over a compute phase (a burst of them stalls the issuing wave until the
   // memory pipeline drains): Rows::prepare() reads the table entries of a tile into
   // registers; Filler::issue_one()/issue() launch the copies of one tensor.  Tensors
   // streamed together (K and V, or Q and dO) share one Rows.
   static constexpr int kRowsPerInst = 64 / NC;
+  static constexpr int kRowStep = kRowsPerInst * kWaves;
+  static constexpr int kInstStep = kRowStep * D * 2;   // LDS bytes between instructions
+  static_assert(kRowStep % 16 == 0, "swizzle period must divide the instruction row step");
   struct Rows {
     uint32_t tab;                    // LDS byte address of table[row of instruction 0]
     uint32_t g[kFillPerWave];        // grid index of the lane's row in each instruction
     __device__ __forceinline__ void init(uint32_t table_lds, int wave, int lane) {
-      tab = table_lds + (wave * kFillPerWave * kRowsPerInst + lane / NC) * 4;
+      tab = table_lds + (wave * kRowsPerInst + lane / NC) * 4;
     }
     // t0: first token of the tile (multiple of kStream)
     __device__ __forceinline__ void prepare(int t0) {
       const uint32_t row0 = tab + t0 * 4;
 #pragma unroll
       for (int i = 0; i < kFillPerWave; ++i)
-        g[i] = *reinterpret_cast<const AERIS_LDS uint32_t*>(row0 + i * kRowsPerInst * 4);
+        g[i] = *reinterpret_cast<const AERIS_LDS uint32_t*>(row0 + i * kRowStep * 4);
     }
   };
   struct Filler {
-    const char* src[kFillPerWave];   // tensor origin of this (batch, head) + lane's chunk
+    const char* src;                 // tensor origin of this (batch, head) + lane's chunk
     uint32_t dst;                    // byte offset of this wave's first instruction in a tile
     uint32_t stride_bytes;
 
     __device__ __forceinline__ void init(const bf16_t* origin, long long tok_stride, int wave,
                                          int lane) {
       stride_bytes = (uint32_t)(tok_stride * 2);
-      dst = wave * kFillPerWave * 1024;
-#pragma unroll
-      for (int i = 0; i < kFillPerWave; ++i) {
-        const int r = (wave * kFillPerWave + i) * kRowsPerInst + lane / NC;
-        const int c = (lane % NC) ^ swz(r);
-        src[i] = reinterpret_cast<const char*>(origin) + c * 16;
-      }
+      dst = wave * 1024;
+      const int r = wave * kRowsPerInst + lane / NC;
+      src = reinterpret_cast<const char*>(origin) + ((lane % NC) ^ swz(r)) * 16;
     }
     // tile: LDS byte address (wave-uniform)
     __device__ __forceinline__ void issue_one(int i, uint32_t tile, const Rows& rows) const {
-      async_copy16(src[i] + (unsigned long long)rows.g[i] * stride_bytes, tile + dst + i * 1024);
+      async_copy16(src + (unsigned long long)rows.g[i] * stride_bytes, tile + dst + i * kInstStep);
     }
     __device__ __forceinline__ void issue(uint32_t tile, const Rows& rows) const {
 #pragma unroll
       for (int i = 0; i < kFillPerWave; ++i) issue_one(i, tile, rows);
+    }
+    // enable: wave-uniform, non-zero = issue
+    __device__ __forceinline__ void issue_one_if(int i, uint32_t tile, const Rows& rows,
+                                                 uint32_t enable) const {
+      async_copy16_if(src + (unsigned long long)rows.g[i] * stride_bytes,
+                      tile + dst + i * kInstStep, enable);
+    }
+    __device__ __forceinline__ void issue_if(uint32_t tile, const Rows& rows,
+                                             uint32_t enable) const {
+#pragma unroll
+      for (int i = 0; i < kFillPerWave; ++i) issue_one_if(i, tile, rows, enable);
     }
   };
 

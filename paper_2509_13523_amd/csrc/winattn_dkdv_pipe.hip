@@ -17,27 +17,8 @@
 #include "winattn_common.hpp"
 #include "winattn_launch.hpp"
 
-// Optional stage timing (development aid, off by default): -DAERIS_STAGE_TIMING makes one
-// wave of one workgroup accumulate the 100 MHz wall clock per pipeline stage into
-// aeris_stage_ticks[], which a test harness reads back with hipMemcpyFromSymbol.
 #ifdef AERIS_STAGE_TIMING
 __device__ unsigned long long aeris_stage_ticks[16];
-#define AERIS_TICK_DECL                                                              \
-  const bool tick_on = blockIdx.x == 8 * 40 + 3 && threadIdx.x == 0;                 \
-  unsigned long long tick_last = wall_clock64(), tick_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#define AERIS_TICK(i)                                 \
-  if (tick_on) {                                      \
-    const unsigned long long t = wall_clock64();      \
-    tick_acc[i] += t - tick_last;                     \
-    tick_last = t;                                    \
-  }
-#define AERIS_TICK_FLUSH \
-  if (tick_on)           \
-    for (int i = 0; i < 8; ++i) aeris_stage_ticks[i] = tick_acc[i];
-#else
-#define AERIS_TICK_DECL
-#define AERIS_TICK(i)
-#define AERIS_TICK_FLUSH
 #endif
 
 namespace aeris {
@@ -316,7 +297,7 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
       st += step;
     }
   }
-  AERIS_TICK_FLUSH
+  AERIS_TICK_FLUSH(aeris_stage_ticks)
 
   if (!rg.valid) return;
   OutT* dkrow = dk + qkv_base + (long long)k_grid * p.qkv_tok;
@@ -360,7 +341,6 @@ int launch_dkdv_pipe128(const KParams& kp, bool out_f32, const void* q, const vo
 
 #ifdef AERIS_STAGE_TIMING
 extern "C" int aeris_debug_read(unsigned long long* out) {
-  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(aeris_stage_ticks),
-                                  16 * sizeof(unsigned long long));
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(aeris_stage_ticks), 128);
 }
 #endif

@@ -14,6 +14,12 @@
 #include "winattn_common.hpp"
 #include "winattn_launch.hpp"
 
+#ifdef AERIS_STAGE_TIMING
+__device__ unsigned long long aeris_fwd_ticks[16];
+extern "C" int aeris_debug_read_fwd(unsigned long long* out) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(aeris_fwd_ticks), 128);
+}
+#endif
 namespace aeris {
 
 template <int D>
@@ -85,42 +91,57 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
   float m_run = -INFINITY;   // running (lagging) row maximum, log2 domain
   float l_run = 0.f;         // this lane's share of the row sum
 
-  // One 32-key block at compile-time LDS offset kOff from buffer 0 / sub-block 0:
-  // every operand address is a per-lane register plus an immediate.
-  auto sub_block = [&](auto off, int sub_lo) __attribute__((always_inline)) {
+  // Schedule of one 32-key block (LDS offsets are compile-time constants, so every
+  // operand address is a per-lane register plus an immediate):
+  //   logits phase   D/16 products S^T = K Q^T, whose K operands were fetched during
+  //                  the previous block; between them the V operands of this block are
+  //                  fetched (they land during the softmax) and copies of the next
+  //                  tile are issued;
+  //   softmax phase  vector work only;
+  //   output phase   D/16 products O^T += V^T P^T; between them the K operands of the
+  //                  NEXT block are fetched and further copies are issued.
+  // The scheduling fences keep the compiler from collapsing the phases again (it
+  // otherwise serialises operand reads and products to save registers).
+  bf16x8 ka[D / 16], va[D / 32][2];
+  f32x16 sacc;
+  union { u32x4 u; bf16x8 h; } pb[2];
+  constexpr int kF = Tl::kFillPerWave;
+
+  auto fetch_k = [&](auto off) __attribute__((always_inline)) {
     constexpr uint32_t kOff = decltype(off)::value;
-    if (rg.skip(sub_lo)) return;   // wave-uniform
-    // ---- operand reads first, products after: LDS latency hides behind the MFMA
-    //      pipeline; the V operands land during the softmax ------------------------
-    bf16x8 ka[D / 16], va[D / 32][2];
 #pragma unroll
     for (int kk = 0; kk < D / 16; ++kk) ka[kk] = Tl::read_rm(la.rm[kk] + kOff);
+  };
+  // en: non-zero if the copies are wanted (wave-uniform)
+  auto logits_phase = [&](auto off, auto with_fill, const typename Tl::Filler& fill,
+                          uint32_t fill_tile, uint32_t en) __attribute__((always_inline)) {
+    constexpr uint32_t kV = decltype(off)::value + Tl::kBytes;
+    constexpr bool kFill = decltype(with_fill)::value != 0;
 #pragma unroll
-    for (int cb = 0; cb < D / 32; ++cb)
+    for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+    sched_fence();
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        constexpr uint32_t kV = kOff + Tl::kBytes;
-        va[cb][c] = Tl::read_tr(la.tr[cb][0] + kV + c * Tl::kGroupBytes,
-                                la.tr[cb][1] + kV + c * Tl::kGroupBytes);
-      }
-    // ---- S^T = K Q^T ---------------------------------------------------------
-    f32x16 s;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) s[i] = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) s = mfma32(ka[kk], qreg[kk], s);
-    // ---- mask ----------------------------------------------------------------
+    for (int kk = 0; kk < D / 16; ++kk) {
+      sacc = mfma32(ka[kk], qreg[kk], sacc);
+      const int cb = kk >> 1, c = kk & 1;
+      va[cb][c] = Tl::read_tr(la.tr[cb][0] + kV + c * Tl::kGroupBytes,
+                              la.tr[cb][1] + kV + c * Tl::kGroupBytes);
+      if (kFill && (kk & 1) && (kk >> 1) < kF) fill.issue_one_if(kk >> 1, fill_tile, rows, en);
+      sched_fence();
+    }
+  };
+  auto softmax_phase = [&](int sub_lo) __attribute__((always_inline)) {
     if (!rg.mask_free(sub_lo)) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int kidx = sub_lo + acc_row(i, g);
-        if (kidx < lo_q || kidx >= hi_q) s[i] = -INFINITY;
+        if (kidx < lo_q || kidx >= hi_q) sacc[i] = -INFINITY;
       }
     }
-    // ---- online softmax (log2 domain, lagging maximum) --------------------------
-    float mx = s[0];
+    // online softmax, log2 domain, lagging maximum
+    float mx = sacc[0];
 #pragma unroll
-    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
+    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sacc[i]);
     mx = wave_half_max(mx) * p.scale_log2;
     const bool grow = mx > m_run + kLazyRescale;
     if (__builtin_expect(__any(grow), 0)) {
@@ -137,42 +158,102 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
     float psum = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.scale_log2, -m_sub));
+      pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], p.scale_log2, -m_sub));
       psum += pv[i];
     }
     l_run += psum;
-    // ---- O^T += V^T P^T ----------------------------------------------------------
-    union { u32x4 u; bf16x8 h; } pb[2];
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
       for (int e = 0; e < 4; ++e) pb[c].u[e] = pack_bf16(pv[8 * c + 2 * e], pv[8 * c + 2 * e + 1]);
+  };
+  auto output_phase = [&](auto k_off, auto with_fill, const typename Tl::Filler& fill,
+                          uint32_t fill_tile, uint32_t en) __attribute__((always_inline)) {
+    constexpr uint32_t kOff = decltype(k_off)::value;
+    constexpr bool kFill = decltype(with_fill)::value != 0;
+    sched_fence();
 #pragma unroll
-    for (int cb = 0; cb < D / 32; ++cb)
-#pragma unroll
-      for (int c = 0; c < 2; ++c) oacc[cb] = mfma32(va[cb][c], pb[c].h, oacc[cb]);
+    for (int j = 0; j < D / 16; ++j) {
+      const int c = j / (D / 32), cb = j % (D / 32);
+      oacc[cb] = mfma32(va[cb][c], pb[c].h, oacc[cb]);
+      ka[j] = Tl::read_rm(la.rm[j] + kOff);
+      if (kFill && (j & 1) && (j >> 1) < kF) fill.issue_one_if(j >> 1, fill_tile, rows, en);
+      sched_fence();
+    }
   };
 
-  // One streamed tile held in buffer kP (compile time); the next one flies into
-  // the other buffer during the math.  One barrier per tile: it publishes tile
-  // kt and retires the readers of tile kt-1, whose buffer the new fill reuses.
+  // Tile kt lives in buffer (kt - kt_begin) & 1.  While it is processed, the V copies
+  // of tile kt+1 are issued (its K copies were issued during tile kt-1); a barrier in
+  // the middle of the second block publishes tile kt+1 and retires the readers of tile
+  // kt, after which the K copies of tile kt+2 go into this tile's buffer.  Copies of
+  // tiles past the end are branched over.
+  const int kt_last = kt_end - 1;
+  AERIS_TICK_DECL
+  auto prepare_after_next = [&](int kt) __attribute__((always_inline)) {
+    rows.prepare((kt + 2 < kt_last ? kt + 2 : kt_last) * kStream);
+  };
+  // A tile in which this wave computes both blocks (masked where needed).
   auto tile_step = [&](auto parity, int kt) __attribute__((always_inline)) {
     constexpr uint32_t kP = decltype(parity)::value;
+    constexpr uint32_t kCur = kP * kBuf, kNext = (1 - kP) * kBuf;
+    const uint32_t has1 = kt + 1 < kt_end, has2 = kt + 2 < kt_end;
+    AERIS_TICK(7)
+    logits_phase(Const<kCur>{}, Const<1>{}, vfill, tiles + kNext + Tl::kBytes, has1);
+    AERIS_TICK(0)
+    prepare_after_next(kt);
+    softmax_phase(kt * kStream);
+    AERIS_TICK(1)
+    output_phase(Const<kCur + Tl::kSubBytes>{}, Const<0>{}, kfill, 0, 0);
+    AERIS_TICK(2)
+    logits_phase(Const<kCur + Tl::kSubBytes>{}, Const<0>{}, vfill, 0, 0);
+    AERIS_TICK(3)
+    softmax_phase(kt * kStream + 32);
+    AERIS_TICK(4)
     wait_async_loads();
     __syncthreads();
-    if (kt + 1 < kt_end) {     // table entries were read one tile ago
-      kfill.issue(tiles + (1 - kP) * kBuf, rows);
-      vfill.issue(tiles + (1 - kP) * kBuf + Tl::kBytes, rows);
-      if (kt + 2 < kt_end) rows.prepare((kt + 2) * kStream);
-    }
-    if (!rg.wave_active) return;
-    sub_block(Const<kP * kBuf>{}, kt * kStream);
-    sub_block(Const<kP * kBuf + Tl::kSubBytes>{}, kt * kStream + 32);
+    AERIS_TICK(5)
+    output_phase(Const<kNext>{}, Const<1>{}, kfill, tiles + kCur, has2);
+    AERIS_TICK(6)
   };
-  for (int kt = kt_begin; kt < kt_end; kt += 2) {
-    tile_step(Const<0>{}, kt);
-    if (kt + 1 < kt_end) tile_step(Const<1>{}, kt + 1);
+  // A tile none of whose keys this wave needs: keep the copies and the barrier going.
+  auto idle_step = [&](int kt) __attribute__((always_inline)) {
+    const uint32_t cur = tiles + ((kt - kt_begin) & 1) * kBuf, next = tiles + kBuf - (cur - tiles);
+    vfill.issue_if(next + Tl::kBytes, rows, kt + 1 < kt_end);
+    prepare_after_next(kt);
+    wait_async_loads();
+    __syncthreads();
+    kfill.issue_if(cur, rows, kt + 2 < kt_end);
+  };
+
+  // This wave's tiles: [wt_lo, wt_hi) inside the workgroup's [kt_begin, kt_end).
+  const int wt_lo = rg.wave_active ? rg.w_lo / kStream : kt_end;
+  const int wt_hi = rg.wave_active ? (rg.w_hi + kStream - 1) / kStream : kt_end;
+
+  wait_async_loads();
+  __syncthreads();
+  kfill.issue_if(tiles + kBuf, rows, kt_begin + 1 < kt_end);
+  int kt = kt_begin;
+  for (; kt < wt_lo; ++kt) idle_step(kt);
+  if (kt < wt_hi) {
+    if ((kt - kt_begin) & 1) {
+      fetch_k(Const<kBuf>{});
+      tile_step(Const<1>{}, kt);
+      ++kt;
+    } else {
+      fetch_k(Const<0>{});
+    }
+    for (; kt + 1 < wt_hi; kt += 2) {
+      tile_step(Const<0>{}, kt);
+      tile_step(Const<1>{}, kt + 1);
+    }
+    if (kt < wt_hi) {
+      tile_step(Const<0>{}, kt);
+      ++kt;
+    }
   }
+  for (; kt < kt_end; ++kt) idle_step(kt);
+  wait_async_loads();
+  AERIS_TICK_FLUSH(aeris_fwd_ticks)
 
   // ---- epilogue: normalise, un-shift/un-partition store -----------------------
   if (!rg.valid) return;
