@@ -199,8 +199,18 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // Row of a 32x32 accumulator tile held in register v by a lane of half g.
 __device__ __forceinline__ int acc_row(int v, int g) { return 8 * (v >> 2) + 4 * g + (v & 3); }
 
+// max over the lane pair (l, l ^ 32).  v_permlane32_swap hands every lane the value
+// of lane l % 32 and the value of lane 32 + l % 32 without a trip through the LDS.
 __device__ __forceinline__ float wave_half_max(float x) {
-  return fmaxf(x, __shfl_xor(x, 32));
+  const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+
+// a + b + acc for a packed bf16 pair (v_dot2c_f32_bf16 against {1, 1}).
+__device__ __forceinline__ float add_bf16_pair(uint32_t pair, float acc) {
+  const uint32_t ones = 0x3F803F80u;
+  return __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2*>(&pair),
+                                         *reinterpret_cast<const bf16x2*>(&ones), acc, false);
 }
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {

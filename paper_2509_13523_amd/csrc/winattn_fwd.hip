@@ -155,17 +155,20 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
     }
     const float m_sub = m_run == -INFINITY ? 0.f : m_run;
     float pv[16];
-    float psum = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < 16; ++i)
       pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], p.scale_log2, -m_sub));
-      psum += pv[i];
-    }
-    l_run += psum;
+    // The row sum is taken over the bf16-rounded probabilities, the ones the second
+    // product multiplies: numerator and denominator then carry the same rounding.
+    float psum = 0.f;
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) pb[c].u[e] = pack_bf16(pv[8 * c + 2 * e], pv[8 * c + 2 * e + 1]);
+      for (int e = 0; e < 4; ++e) {
+        pb[c].u[e] = pack_bf16(pv[8 * c + 2 * e], pv[8 * c + 2 * e + 1]);
+        psum = add_bf16_pair(pb[c].u[e], psum);
+      }
+    l_run += psum;
   };
   auto output_phase = [&](auto k_off, auto with_fill, const typename Tl::Filler& fill,
                           uint32_t fill_tile, uint32_t en) __attribute__((always_inline)) {
