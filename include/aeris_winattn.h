@@ -64,7 +64,8 @@ enum {
   AERIS_ERR_WORKSPACE_TOO_SMALL = -8,
   AERIS_ERR_WINDOW_TOO_LARGE = -9,     /* win_h*win_w > AERIS_MAX_WINDOW_TOKENS     */
   AERIS_ERR_BAD_DTYPE = -10,
-  AERIS_ERR_HIP_LAUNCH = -11           /* hipGetLastError() after a launch          */
+  AERIS_ERR_HIP_LAUNCH = -11,          /* hipGetLastError() after a launch          */
+  AERIS_ERR_BAD_ROPE = -12             /* rotary base <= 1 or unknown position mode */
 };
 
 /* Largest window (tokens) the kernels' on-chip offset table holds. */
@@ -132,6 +133,64 @@ int aeris_winattn_bwd_stages(const aeris_winattn_params* p, const void* q, const
                              const void* v, const void* o, const float* lse, const void* d_o,
                              void* dq, void* dk, void* dv, void* workspace,
                              size_t workspace_bytes, void* hip_stream, unsigned stages);
+
+/*
+ * Rotary embedding of queries and keys (Model Architecture section: queries and keys
+ * pass through an axial-frequency 2-D rotary position embedding before the dot-product
+ * attention).  The paper gives no formula; this library takes the axial-frequency form
+ * of the work it cites:
+ *   - the head_dim channels of a head are head_dim/2 pairs (2j, 2j+1);
+ *   - theta_t = base^(-t / (head_dim/4)), t = 0 .. head_dim/4 - 1;
+ *   - pair 2t turns by theta_t * (longitude position), pair 2t+1 by
+ *     theta_t * (latitude position); a pair (a, b) turns as the complex number a + ib;
+ *   - positions: AERIS_ROPE_POS_WINDOW: coordinates inside the attention window in the
+ *     shifted frame, ((y - shift_h) mod H_lat) mod win_h and likewise for x;
+ *     AERIS_ROPE_POS_GRID: grid coordinates (y, x).
+ * Rotated values are rounded to bf16, the type the products multiply in.
+ */
+enum { AERIS_ROPE_POS_WINDOW = 0, AERIS_ROPE_POS_GRID = 1 };
+typedef struct {
+  float base;        /* > 1 */
+  int32_t positions; /* AERIS_ROPE_POS_* */
+} aeris_rope_params;
+
+/*
+ * y = R x (inverse == 0) or y = R^T x (inverse != 0) for one tensor.
+ *   x : bf16 [B, H_lat, W_lon, heads, head_dim] with the qkv strides of p, read-only
+ *   y : bf16, same layout, overwritten; may equal x (in place)
+ * Elementwise; bound by memory traffic.
+ */
+int aeris_rope2d_apply(const aeris_winattn_params* p, const aeris_rope_params* r, const void* x,
+                       void* y, int32_t inverse, void* hip_stream);
+
+/* Bytes of workspace of the two calls below: room for rotated copies of k (forward),
+ * of q and k plus the backward workspace (backward).  0 if the parameters are invalid. */
+size_t aeris_winattn_rope_fwd_workspace_bytes(const aeris_winattn_params* p);
+size_t aeris_winattn_rope_bwd_workspace_bytes(const aeris_winattn_params* p);
+
+/*
+ * aeris_winattn_fwd on rotated queries and keys: o, lse = attention(R q, R k, v).
+ * The keys stream from global memory into the LDS without passing registers, so they
+ * are rotated once into the workspace by a memory-bound pass; the queries, which the
+ * kernel keeps in registers, are rotated as they are loaded.  Arguments as
+ * aeris_winattn_fwd; workspace: >= aeris_winattn_rope_fwd_workspace_bytes(p) bytes,
+ * 16-byte aligned, contents undefined before and after.
+ */
+int aeris_winattn_rope_fwd(const aeris_winattn_params* p, const aeris_rope_params* r,
+                           const void* q, const void* k, const void* v, void* o, float* lse,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward of aeris_winattn_rope_fwd: gradients with respect to the UNROTATED q and k
+ * (dq = R^T dq', dk = R^T dk', rotated back in the epilogues of the kernels that
+ * accumulate them) and v.  q, k are the unrotated inputs; o, lse the outputs of
+ * aeris_winattn_rope_fwd.  Other arguments as aeris_winattn_bwd; workspace:
+ * >= aeris_winattn_rope_bwd_workspace_bytes(p) bytes.
+ */
+int aeris_winattn_rope_bwd(const aeris_winattn_params* p, const aeris_rope_params* r,
+                           const void* q, const void* k, const void* v, const void* o,
+                           const float* lse, const void* d_o, void* dq, void* dk, void* dv,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Checks a parameter block without launching (host only): AERIS_OK or an error. */
 int aeris_winattn_validate(const aeris_winattn_params* p);

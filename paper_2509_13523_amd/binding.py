@@ -13,10 +13,14 @@ LIB_PATH = os.path.join(_HERE, "libaeris_winattn.so")
 AERIS_MASK_NONE, AERIS_MASK_LAT, AERIS_MASK_SWIN = 0, 1, 2
 AERIS_DT_BF16, AERIS_DT_F32 = 0, 1
 AERIS_BWD_DELTA, AERIS_BWD_DQ, AERIS_BWD_DKDV, AERIS_BWD_ALL = 1, 2, 4, 7
+AERIS_ROPE_POS_WINDOW, AERIS_ROPE_POS_GRID = 0, 1
 
 EXPORTS = ("aeris_winattn_fwd", "aeris_winattn_bwd", "aeris_winattn_bwd_stages",
            "aeris_winattn_bwd_workspace_bytes",
-           "aeris_winattn_validate", "aeris_winattn_strerror", "aeris_winattn_version")
+           "aeris_winattn_validate", "aeris_winattn_strerror", "aeris_winattn_version",
+           "aeris_rope2d_apply", "aeris_winattn_rope_fwd_workspace_bytes",
+           "aeris_winattn_rope_bwd_workspace_bytes", "aeris_winattn_rope_fwd",
+           "aeris_winattn_rope_bwd")
 
 
 class aeris_winattn_params(ctypes.Structure):
@@ -28,6 +32,10 @@ class aeris_winattn_params(ctypes.Structure):
                 ("out_dtype", ctypes.c_int32),
                 ("qkv_tok_stride", ctypes.c_int64), ("qkv_head_stride", ctypes.c_int64),
                 ("o_tok_stride", ctypes.c_int64), ("o_head_stride", ctypes.c_int64)]
+
+
+class aeris_rope_params(ctypes.Structure):
+    _fields_ = [("base", ctypes.c_float), ("positions", ctypes.c_int32)]
 
 
 class AerisError(RuntimeError):
@@ -67,6 +75,18 @@ def load():
     lib.aeris_winattn_strerror.restype = ctypes.c_char_p
     lib.aeris_winattn_version.argtypes = []
     lib.aeris_winattn_version.restype = ctypes.c_int
+    R = ctypes.POINTER(aeris_rope_params)
+    lib.aeris_rope2d_apply.argtypes = [P, R, vp, vp, ctypes.c_int32, vp]
+    lib.aeris_rope2d_apply.restype = ctypes.c_int
+    lib.aeris_winattn_rope_fwd_workspace_bytes.argtypes = [P]
+    lib.aeris_winattn_rope_fwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.aeris_winattn_rope_bwd_workspace_bytes.argtypes = [P]
+    lib.aeris_winattn_rope_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.aeris_winattn_rope_fwd.argtypes = [P, R, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.aeris_winattn_rope_fwd.restype = ctypes.c_int
+    lib.aeris_winattn_rope_bwd.argtypes = [P, R, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                           ctypes.c_size_t, vp]
+    lib.aeris_winattn_rope_bwd.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -161,4 +181,76 @@ def aeris_winattn_bwd_stages(q, k, v, o, lse, d_o, win, shift, mask=AERIS_MASK_N
         rc = lib.aeris_winattn_bwd_stages(*args, stages)
     if rc != 0:
         raise AerisError(rc, "aeris_winattn_bwd")
+    return dq, dk, dv
+
+
+def aeris_rope2d_apply(x, win, shift, base, positions, inverse=False, y=None):
+    """Rotary embedding of one contiguous bf16 [B,H,W,heads,d] device tensor; returns y."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.bfloat16 and x.is_contiguous()
+    p = make_params(x.shape, win, shift)
+    r = aeris_rope_params(float(base), int(positions))
+    if y is None:
+        y = torch.empty_like(x)
+    rc = load().aeris_rope2d_apply(ctypes.byref(p), ctypes.byref(r), x.data_ptr(), y.data_ptr(),
+                                   1 if inverse else 0, _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_rope2d_apply")
+    return y
+
+
+def aeris_winattn_rope_fwd_workspace_bytes(params):
+    return load().aeris_winattn_rope_fwd_workspace_bytes(ctypes.byref(params))
+
+
+def aeris_winattn_rope_bwd_workspace_bytes(params):
+    return load().aeris_winattn_rope_bwd_workspace_bytes(ctypes.byref(params))
+
+
+def aeris_winattn_rope_fwd(q, k, v, win, shift, base, positions, mask=AERIS_MASK_NONE, scale=None,
+                           out_dtype=AERIS_DT_BF16, o=None, lse=None, workspace=None):
+    """Attention on rotated queries and keys.  Returns (o, lse)."""
+    import torch
+    B, H, W, nh, d = q.shape
+    for t in (q, k, v):
+        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.shape == q.shape
+    p = make_params(q.shape, win, shift, mask, scale, out_dtype)
+    r = aeris_rope_params(float(base), int(positions))
+    if o is None:
+        o = torch.empty(q.shape, dtype=_torch_out_dtype(out_dtype), device=q.device)
+    if lse is None:
+        lse = torch.empty((B, nh, H, W), dtype=torch.float32, device=q.device)
+    need = aeris_winattn_rope_fwd_workspace_bytes(p)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    rc = load().aeris_winattn_rope_fwd(ctypes.byref(p), ctypes.byref(r), q.data_ptr(),
+                                       k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                       workspace.data_ptr(), workspace.numel(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_winattn_rope_fwd")
+    return o, lse
+
+
+def aeris_winattn_rope_bwd(q, k, v, o, lse, d_o, win, shift, base, positions,
+                           mask=AERIS_MASK_NONE, scale=None, out_dtype=AERIS_DT_BF16,
+                           workspace=None):
+    """Gradients with respect to the unrotated q, k and v.  Returns (dq, dk, dv)."""
+    import torch
+    p = make_params(q.shape, win, shift, mask, scale, out_dtype)
+    r = aeris_rope_params(float(base), int(positions))
+    odt = _torch_out_dtype(out_dtype)
+    assert o.dtype == odt and d_o.dtype == torch.bfloat16 and lse.dtype == torch.float32
+    for t in (q, k, v, o, d_o, lse):
+        assert t.is_cuda and t.is_contiguous()
+    dq, dk, dv = [torch.empty(q.shape, dtype=odt, device=q.device) for _ in range(3)]
+    need = aeris_winattn_rope_bwd_workspace_bytes(p)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    rc = load().aeris_winattn_rope_bwd(ctypes.byref(p), ctypes.byref(r), q.data_ptr(),
+                                       k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                       d_o.data_ptr(), dq.data_ptr(), dk.data_ptr(),
+                                       dv.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                       _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_winattn_rope_bwd")
     return dq, dk, dv

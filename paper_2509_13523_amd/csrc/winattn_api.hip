@@ -62,11 +62,31 @@ aeris::KParams derive(const aeris_winattn_params* p, const Strides& s) {
   k.n_pairs = k.B * k.nWy * k.nWx * k.nh;
   k.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.f / sqrtf((float)p->head_dim);
   k.scale_log2 = k.scale * 1.4426950408889634f;
-  k.qkv_tok = s.qkv_tok;
-  k.qkv_head = s.qkv_head;
+  k.qkv_tok = k.q_tok = k.k_tok = s.qkv_tok;
+  k.qkv_head = k.q_head = k.k_head = s.qkv_head;
   k.o_tok = s.o_tok;
   k.o_head = s.o_head;
+  k.rope = 0;
+  k.rope_pos = 0;
+  k.rope_c = 0.f;
   return k;
+}
+
+int resolve_rope(const aeris_winattn_params* p, const aeris_rope_params* r, aeris::KParams* k) {
+  if (!r) return AERIS_ERR_NULL_POINTER;
+  if (!(r->base > 1.f) || !isfinite(r->base)) return AERIS_ERR_BAD_ROPE;
+  if (r->positions != AERIS_ROPE_POS_WINDOW && r->positions != AERIS_ROPE_POS_GRID)
+    return AERIS_ERR_BAD_ROPE;
+  k->rope = 1;
+  k->rope_pos = r->positions;
+  k->rope_c = log2f(r->base) / (float)(p->head_dim / 4);
+  return AERIS_OK;
+}
+
+// Bytes of one compact [B, H, W, heads, head_dim] bf16 tensor, rounded up to 256.
+size_t dense_tensor_bytes(const aeris_winattn_params* p) {
+  const size_t n = (size_t)p->B * p->H_lat * p->W_lon * p->heads * p->head_dim * 2;
+  return (n + 255) & ~(size_t)255;
 }
 
 bool misaligned(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15) != 0; }
@@ -130,6 +150,102 @@ int aeris_winattn_bwd_stages(const aeris_winattn_params* p, const void* q, const
   return AERIS_OK;
 }
 
+int aeris_rope2d_apply(const aeris_winattn_params* p, const aeris_rope_params* r, const void* x,
+                       void* y, int32_t inverse, void* hip_stream) {
+  Strides s;
+  int rc = resolve(p, &s);
+  if (rc != AERIS_OK) return rc;
+  aeris::KParams kp = derive(p, s);
+  rc = resolve_rope(p, r, &kp);
+  if (rc != AERIS_OK) return rc;
+  if (!x || !y) return AERIS_ERR_NULL_POINTER;
+  if (misaligned(x) || misaligned(y)) return AERIS_ERR_MISALIGNED;
+  if (aeris::launch_rope(kp, p->head_dim, x, s.qkv_tok, s.qkv_head, y, s.qkv_tok, s.qkv_head,
+                         inverse != 0, static_cast<hipStream_t>(hip_stream)) != 0)
+    return AERIS_ERR_HIP_LAUNCH;
+  return AERIS_OK;
+}
+
+size_t aeris_winattn_rope_fwd_workspace_bytes(const aeris_winattn_params* p) {
+  Strides s;
+  if (resolve(p, &s) != AERIS_OK) return 0;
+  return dense_tensor_bytes(p);
+}
+
+size_t aeris_winattn_rope_bwd_workspace_bytes(const aeris_winattn_params* p) {
+  Strides s;
+  if (resolve(p, &s) != AERIS_OK) return 0;
+  return 2 * dense_tensor_bytes(p) + aeris::bwd_workspace_bytes(derive(p, s));
+}
+
+int aeris_winattn_rope_fwd(const aeris_winattn_params* p, const aeris_rope_params* r,
+                           const void* q, const void* k, const void* v, void* o, float* lse,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Strides s;
+  int rc = resolve(p, &s);
+  if (rc != AERIS_OK) return rc;
+  aeris::KParams kp = derive(p, s);
+  rc = resolve_rope(p, r, &kp);
+  if (rc != AERIS_OK) return rc;
+  if (!q || !k || !v || !o || !lse || !workspace) return AERIS_ERR_NULL_POINTER;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) ||
+      misaligned(workspace))
+    return AERIS_ERR_MISALIGNED;
+  if (workspace_bytes < aeris_winattn_rope_fwd_workspace_bytes(p))
+    return AERIS_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  // rotated keys, compact layout
+  const long long d = p->head_dim, dense_tok = (long long)p->heads * d;
+  if (aeris::launch_rope(kp, p->head_dim, k, s.qkv_tok, s.qkv_head, workspace, dense_tok, d, false,
+                         stream) != 0)
+    return AERIS_ERR_HIP_LAUNCH;
+  kp.k_tok = dense_tok;
+  kp.k_head = d;
+  if (aeris::launch_fwd(kp, p->head_dim, p->out_dtype == AERIS_DT_F32, q, workspace, v, o, lse,
+                        stream) != 0)
+    return AERIS_ERR_HIP_LAUNCH;
+  return AERIS_OK;
+}
+
+int aeris_winattn_rope_bwd(const aeris_winattn_params* p, const aeris_rope_params* r,
+                           const void* q, const void* k, const void* v, const void* o,
+                           const float* lse, const void* d_o, void* dq, void* dk, void* dv,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Strides s;
+  int rc = resolve(p, &s);
+  if (rc != AERIS_OK) return rc;
+  aeris::KParams kp = derive(p, s);
+  rc = resolve_rope(p, r, &kp);
+  if (rc != AERIS_OK) return rc;
+  if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !workspace)
+    return AERIS_ERR_NULL_POINTER;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) ||
+      misaligned(d_o) || misaligned(dq) || misaligned(dk) || misaligned(dv) ||
+      misaligned(workspace))
+    return AERIS_ERR_MISALIGNED;
+  if (workspace_bytes < aeris_winattn_rope_bwd_workspace_bytes(p))
+    return AERIS_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  // workspace: rotated q | rotated k | statistics of the backward kernels
+  const size_t tensor = dense_tensor_bytes(p);
+  char* ws = static_cast<char*>(workspace);
+  void* q_rot = ws;
+  void* k_rot = ws + tensor;
+  float* stats = reinterpret_cast<float*>(ws + 2 * tensor);
+  const long long d = p->head_dim, dense_tok = (long long)p->heads * d;
+  if (aeris::launch_rope(kp, p->head_dim, q, s.qkv_tok, s.qkv_head, q_rot, dense_tok, d, false,
+                         stream) != 0 ||
+      aeris::launch_rope(kp, p->head_dim, k, s.qkv_tok, s.qkv_head, k_rot, dense_tok, d, false,
+                         stream) != 0)
+    return AERIS_ERR_HIP_LAUNCH;
+  kp.q_tok = kp.k_tok = dense_tok;
+  kp.q_head = kp.k_head = d;
+  if (aeris::launch_bwd(kp, p->head_dim, p->out_dtype == AERIS_DT_F32, q_rot, k_rot, v, o, lse,
+                        d_o, dq, dk, dv, stats, stream, AERIS_BWD_ALL) != 0)
+    return AERIS_ERR_HIP_LAUNCH;
+  return AERIS_OK;
+}
+
 const char* aeris_winattn_strerror(int code) {
   switch (code) {
     case AERIS_OK: return "ok";
@@ -144,10 +260,11 @@ const char* aeris_winattn_strerror(int code) {
     case AERIS_ERR_WINDOW_TOO_LARGE: return "window has more tokens than AERIS_MAX_WINDOW_TOKENS";
     case AERIS_ERR_BAD_DTYPE: return "unknown output dtype";
     case AERIS_ERR_HIP_LAUNCH: return "HIP kernel launch failed";
+    case AERIS_ERR_BAD_ROPE: return "rotary base must be > 1 and the position mode known";
   }
   return "unknown error code";
 }
 
-int aeris_winattn_version(void) { return 100; }
+int aeris_winattn_version(void) { return 110; }
 
 }  // extern "C"

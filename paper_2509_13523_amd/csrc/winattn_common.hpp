@@ -44,8 +44,15 @@ struct KParams {
   int n_pairs;         // B * nWy * nWx * nh
   float scale;         // softmax scale
   float scale_log2;    // scale * log2(e)
-  long long qkv_tok, qkv_head;  // element strides of q,k,v,dq,dk,dv
+  long long qkv_tok, qkv_head;  // element strides of v and of dq, dk, dv
+  long long q_tok, q_head;      // element strides of the q the kernel reads
+  long long k_tok, k_head;      // element strides of the k the kernel reads
   long long o_tok, o_head;      // element strides of o, dO
+  // Rotary embedding of queries and keys (Model Architecture section; off when rope == 0).
+  int rope;            // 1: the resident q of the forward kernel is rotated as it is loaded,
+                       //    dq and dk are rotated back as they are stored
+  int rope_pos;        // AERIS_ROPE_POS_*
+  float rope_c;        // log2(base) / (head_dim / 4): theta_t = 2^(-t * rope_c)
 };
 
 // Bytes of the per-window token table: one int per token, padded to a whole
@@ -206,17 +213,78 @@ __device__ __forceinline__ float wave_half_max(float x) {
   return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
 }
 
-// a + b + acc for a packed bf16 pair (v_dot2c_f32_bf16 against {1, 1}).
-__device__ __forceinline__ float add_bf16_pair(uint32_t pair, float acc) {
-  const uint32_t ones = 0x3F803F80u;
-  return __builtin_amdgcn_fdot2_f32_bf16(*reinterpret_cast<const bf16x2*>(&pair),
-                                         *reinterpret_cast<const bf16x2*>(&ones), acc, false);
-}
-
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   f32x2 v = {lo, hi};
   bf16x2 r = __builtin_convertvector(v, bf16x2);
   return *reinterpret_cast<uint32_t*>(&r);
+}
+
+// ----------------------------------------------------------------------------
+// Axial-frequency 2-D rotary embedding (Model Architecture section).  Channel pair
+// j = (2j, 2j+1) of a head turns by theta_t * position, t = j / 2, theta_t =
+// base^(-t / (d/4)); even pairs use the longitude position, odd pairs the latitude
+// position.  Positions are grid coordinates, or coordinates inside the window in the
+// shifted frame.
+// ----------------------------------------------------------------------------
+__device__ __forceinline__ void rope_position(const KParams& p, int grid_index, float& p_lat,
+                                              float& p_lon) {
+  int y = grid_index / p.W;
+  int x = grid_index - y * p.W;
+  if (p.rope_pos == 0) {
+    y -= p.s_h;
+    if (y < 0) y += p.H;
+    y %= p.ws_h;
+    x -= p.s_w;
+    if (x < 0) x += p.W;
+    x %= p.ws_w;
+  }
+  p_lat = (float)y;
+  p_lon = (float)x;
+}
+
+// cos and sin of theta_t * pos.  The angle is formed in revolutions with the rounding
+// error of the product recovered by an fma, and reduced by fract() before the hardware
+// sine/cosine, so the error stays near 1e-7 of a revolution at any position.
+__device__ __forceinline__ void rope_cos_sin(float pos, int t, float c, float& cs, float& sn) {
+  const float w = __builtin_amdgcn_exp2f(-(float)t * c) * 0.15915494309189535f;
+  const float hi = pos * w;
+  const float lo = __builtin_fmaf(pos, w, -hi);
+  const float rev = __builtin_amdgcn_fractf(hi) + lo;
+  cs = __builtin_amdgcn_cosf(rev);
+  sn = __builtin_amdgcn_sinf(rev);
+}
+
+// Turns four consecutive pairs (eight channels starting at channel ch0, a multiple of 8).
+__device__ __forceinline__ bf16x8 rope_rotate8(bf16x8 v, int ch0, float p_lat, float p_lon, float c,
+                                               bool inverse) {
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int j = (ch0 >> 1) + e;
+    float cs, sn;
+    rope_cos_sin((e & 1) ? p_lat : p_lon, j >> 1, c, cs, sn);
+    if (inverse) sn = -sn;
+    const float a = (float)v[2 * e], b = (float)v[2 * e + 1];
+    r[2 * e] = (bf16_t)__builtin_fmaf(a, cs, -(b * sn));
+    r[2 * e + 1] = (bf16_t)__builtin_fmaf(a, sn, b * cs);
+  }
+  return r;
+}
+
+// Turns the two pairs (a0, a1), (a2, a3) at channels ch0 .. ch0+3 (ch0 a multiple of 4)
+// back by their angles: the transpose of the embedding, applied to a gradient.
+__device__ __forceinline__ void rope_unrotate4(float& a0, float& a1, float& a2, float& a3, int ch0,
+                                               float p_lat, float p_lon, float c) {
+  const int t = ch0 >> 2;
+  float cs, sn;
+  rope_cos_sin(p_lon, t, c, cs, sn);
+  const float b0 = __builtin_fmaf(a1, sn, a0 * cs), b1 = __builtin_fmaf(-a0, sn, a1 * cs);
+  rope_cos_sin(p_lat, t, c, cs, sn);
+  const float b2 = __builtin_fmaf(a3, sn, a2 * cs), b3 = __builtin_fmaf(-a2, sn, a3 * cs);
+  a0 = b0;
+  a1 = b1;
+  a2 = b2;
+  a3 = b3;
 }
 
 // ----------------------------------------------------------------------------

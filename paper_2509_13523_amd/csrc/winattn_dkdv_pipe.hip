@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
   typename Tl::Rows rows;
   typename Tl::Filler qfill, dofill;
   rows.init(table, wave, lane);
-  qfill.init(q + qkv_base, p.qkv_tok, wave, lane);
+  qfill.init(q + ((long long)win.b * plane) * p.q_tok + (long long)win.head * p.q_head, p.q_tok, wave, lane);
   dofill.init(d_o + o_base, p.o_tok, wave, lane);
   const float* stat_src = (wave == 0 ? lse2v : delta) + (long long)pair * p.T + lane;
   // launches the fill of tile t0, whose table entries `rows` holds
@@ -85,7 +85,8 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
 
   bf16x8 kreg[kNK], vreg[kNK];
   {
-    const bf16_t* krow = k + qkv_base + (long long)k_grid * p.qkv_tok + 8 * g;
+    const bf16_t* krow = k + ((long long)win.b * plane) * p.k_tok + (long long)win.head * p.k_head +
+                         (long long)k_grid * p.k_tok + 8 * g;
     const bf16_t* vrow = v + qkv_base + (long long)k_grid * p.qkv_tok + 8 * g;
 #pragma unroll
     for (int kk = 0; kk < kNK; ++kk) {
@@ -302,13 +303,18 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
   if (!rg.valid) return;
   OutT* dkrow = dk + qkv_base + (long long)k_grid * p.qkv_tok;
   OutT* dvrow = dv + qkv_base + (long long)k_grid * p.qkv_tok;
+  float p_lat = 0.f, p_lon = 0.f;
+  if (p.rope) rope_position(p, k_grid, p_lat, p_lon);
 #pragma unroll
   for (int cb = 0; cb < D / 32; ++cb)
 #pragma unroll
     for (int vq = 0; vq < 4; ++vq) {
       const int ch = cb * 32 + 8 * vq + 4 * g;
-      store4(dkrow + ch, dkacc[cb][4 * vq] * p.scale, dkacc[cb][4 * vq + 1] * p.scale,
-             dkacc[cb][4 * vq + 2] * p.scale, dkacc[cb][4 * vq + 3] * p.scale);
+      float a0 = dkacc[cb][4 * vq] * p.scale, a1 = dkacc[cb][4 * vq + 1] * p.scale,
+            a2 = dkacc[cb][4 * vq + 2] * p.scale, a3 = dkacc[cb][4 * vq + 3] * p.scale;
+      // gradient with respect to the unrotated key: turn the pairs back
+      if (p.rope) rope_unrotate4(a0, a1, a2, a3, ch, p_lat, p_lon, p.rope_c);
+      store4(dkrow + ch, a0, a1, a2, a3);
       store4(dvrow + ch, dvacc[cb][4 * vq], dvacc[cb][4 * vq + 1], dvacc[cb][4 * vq + 2],
              dvacc[cb][4 * vq + 3]);
     }

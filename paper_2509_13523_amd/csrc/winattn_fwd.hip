@@ -51,7 +51,9 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
   const int qi = lane & 31, g = lane >> 5;
 
   const long long plane = (long long)p.H * p.W;
-  const long long qkv_base = ((long long)win.b * plane) * p.qkv_tok + (long long)win.head * p.qkv_head;
+  const long long q_base = ((long long)win.b * plane) * p.q_tok + (long long)win.head * p.q_head;
+  const long long k_base = ((long long)win.b * plane) * p.k_tok + (long long)win.head * p.k_head;
+  const long long v_base = ((long long)win.b * plane) * p.qkv_tok + (long long)win.head * p.qkv_head;
 
   // ---- this lane's query ----------------------------------------------------
   Ranges rg;
@@ -64,8 +66,8 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
   typename Tl::Rows rows;
   typename Tl::Filler kfill, vfill;
   rows.init(table, wave, lane);
-  kfill.init(k + qkv_base, p.qkv_tok, wave, lane);
-  vfill.init(v + qkv_base, p.qkv_tok, wave, lane);
+  kfill.init(k + k_base, p.k_tok, wave, lane);
+  vfill.init(v + v_base, p.qkv_tok, wave, lane);
   rows.prepare(kt_begin * kStream);
   kfill.issue(tiles, rows);
   vfill.issue(tiles + Tl::kBytes, rows);
@@ -73,10 +75,17 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
 
   bf16x8 qreg[D / 16];
   {
-    const bf16_t* qrow = q + qkv_base + (long long)q_grid * p.qkv_tok + 8 * g;
+    const bf16_t* qrow = q + q_base + (long long)q_grid * p.q_tok + 8 * g;
 #pragma unroll
     for (int kk = 0; kk < D / 16; ++kk)
       qreg[kk] = *reinterpret_cast<const bf16x8*>(qrow + kk * 16);
+    if (p.rope) {   // rotary embedding fused into the load of the resident queries
+      float p_lat, p_lon;
+      rope_position(p, q_grid, p_lat, p_lon);
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk)
+        qreg[kk] = rope_rotate8(qreg[kk], kk * 16 + 8 * g, p_lat, p_lon, p.rope_c, false);
+    }
   }
   typename Tl::Lanes la;
   la.init(tiles, lane);
@@ -155,20 +164,17 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
     }
     const float m_sub = m_run == -INFINITY ? 0.f : m_run;
     float pv[16];
+    float psum = 0.f;   // in fp32 over the unrounded probabilities: the saved LSE stays exact
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
+    for (int i = 0; i < 16; ++i) {
       pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], p.scale_log2, -m_sub));
-    // The row sum is taken over the bf16-rounded probabilities, the ones the second
-    // product multiplies: numerator and denominator then carry the same rounding.
-    float psum = 0.f;
+      psum += pv[i];
+    }
+    l_run += psum;
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        pb[c].u[e] = pack_bf16(pv[8 * c + 2 * e], pv[8 * c + 2 * e + 1]);
-        psum = add_bf16_pair(pb[c].u[e], psum);
-      }
-    l_run += psum;
+      for (int e = 0; e < 4; ++e) pb[c].u[e] = pack_bf16(pv[8 * c + 2 * e], pv[8 * c + 2 * e + 1]);
   };
   auto output_phase = [&](auto k_off, auto with_fill, const typename Tl::Filler& fill,
                           uint32_t fill_tile, uint32_t en) __attribute__((always_inline)) {

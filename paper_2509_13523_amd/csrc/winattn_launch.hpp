@@ -19,6 +19,11 @@ int launch_dkdv_pipe128(const KParams& kp, bool out_f32, const void* q, const vo
                         const void* v, const void* d_o, const float* delta, const float* lse2,
                         void* dk, void* dv, hipStream_t stream);
 
+// y = rotary embedding of x (inverse: the rotation by the negated angles); both
+// [B, H, W, heads, head_dim] bf16 with the given element strides.  Uses kp.rope_pos, kp.rope_c.
+int launch_rope(const KParams& kp, int head_dim, const void* x, long long x_tok, long long x_head,
+                void* y, long long y_tok, long long y_head, bool inverse, hipStream_t stream);
+
 // Bytes of device workspace launch_bwd needs for these parameters.
 size_t bwd_workspace_bytes(const KParams& kp);
 

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_exports_match_header():
     text = open(os.path.join(ROOT, "include", "aeris_winattn.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(aeris_winattn_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(aeris_[a-z0-9_]+)\s*\(", text))
     assert declared == set(B.EXPORTS)
     lib = B.load()
     for name in declared:
@@ -24,7 +24,7 @@ def test_exports_match_header():
 def test_version_and_strerror():
     assert B.aeris_winattn_version() >= 100
     assert B.aeris_winattn_strerror(0) == "ok"
-    for code in range(-11, 0):
+    for code in range(-12, 0):
         assert B.aeris_winattn_strerror(code) != "unknown error code"
     assert B.aeris_winattn_strerror(-99) == "unknown error code"
 
@@ -72,3 +72,29 @@ def test_null_and_misaligned_pointers_rejected_before_launch():
     bad = B.make_params(**dict(good(), win=(7, 8)))
     assert B.aeris_winattn_bwd_workspace_bytes(bad) == 0
     assert lib.aeris_winattn_bwd(ctypes.byref(bad), *args, need, None) == -3
+
+
+def test_rope_arguments_rejected_before_launch():
+    lib = B.load()
+    p = B.make_params((1, 64, 128, 4, 32), (8, 8), (4, 4))
+    buf = (ctypes.c_char * 64)()
+    a = ctypes.addressof(buf)
+    a += (-a) % 16
+    for base, pos, code in ((1.0, 0, -12), (0.0, 0, -12), (-5.0, 1, -12), (100.0, 2, -12),
+                            (float("inf"), 0, -12)):
+        r = B.aeris_rope_params(base, pos)
+        assert lib.aeris_rope2d_apply(ctypes.byref(p), ctypes.byref(r), a, a, 0, None) == code
+        assert lib.aeris_winattn_rope_fwd(ctypes.byref(p), ctypes.byref(r), a, a, a, a, a, a,
+                                          1 << 40, None) == code
+    r = B.aeris_rope_params(100.0, 0)
+    assert lib.aeris_rope2d_apply(ctypes.byref(p), None, a, a, 0, None) == -1
+    assert lib.aeris_rope2d_apply(ctypes.byref(p), ctypes.byref(r), None, a, 0, None) == -1
+    assert lib.aeris_rope2d_apply(ctypes.byref(p), ctypes.byref(r), a + 2, a, 0, None) == -7
+    # workspace sizes: one compact bf16 tensor forward; two of them plus the statistics backward
+    tensor = 1 * 64 * 128 * 4 * 32 * 2
+    assert B.aeris_winattn_rope_fwd_workspace_bytes(p) == tensor
+    assert B.aeris_winattn_rope_bwd_workspace_bytes(p) == 2 * tensor + B.aeris_winattn_bwd_workspace_bytes(p)
+    assert lib.aeris_winattn_rope_fwd(ctypes.byref(p), ctypes.byref(r), a, a, a, a, a, a,
+                                      tensor - 1, None) == -8
+    assert lib.aeris_winattn_rope_bwd(ctypes.byref(p), ctypes.byref(r), a, a, a, a, a, a, a, a, a,
+                                      a, 2 * tensor, None) == -8

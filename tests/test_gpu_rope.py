@@ -1,0 +1,129 @@
+"""GPU parity of the rotary-embedding entry points against oracle/rope_oracle.py.
+
+The kernels multiply in bf16, so the rotated queries and keys are rounded to bf16 before
+the logits.  The oracle is given the same rounding through its ``round_fn`` hook (it never
+rounds by itself); the attention tolerances are then the ones of tests/test_gpu_parity.py.
+The rotation itself is checked element by element: a rotated pair may differ from the fp64
+value by the bf16 rounding of its components (2^-9 relative each) plus the error of the
+hardware sine and cosine, together bounded by 2^-8 of the pair's length.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rope_oracle as ro
+from oracle import winattn_oracle as orc
+from paper_2509_13523_amd import binding as B
+from paper_2509_13523_amd import synth
+from test_gpu_parity import LSE_ABS, check, to_dev, to_f64
+
+pytestmark = pytest.mark.gpu
+
+MODES = [B.AERIS_ROPE_POS_WINDOW, B.AERIS_ROPE_POS_GRID]
+
+
+def round_bf16(x):
+    return synth.bf16_bits_to_f64(synth.f32_to_bf16_bits(x.astype(np.float32)))
+
+
+def pair_error_ok(got, ref):
+    err2 = (got[..., 0::2] - ref[..., 0::2]) ** 2 + (got[..., 1::2] - ref[..., 1::2]) ** 2
+    len2 = ref[..., 0::2] ** 2 + ref[..., 1::2] ** 2
+    return bool((err2 <= (2.0 ** -8) ** 2 * len2 + 1e-12).all())
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("shape,win,shift", [
+    ((2, 24, 36, 3, 32), (12, 12), (6, 6)),
+    ((1, 60, 1440, 1, 64), (60, 60), (30, 30)),     # longitude positions up to 1439
+    ((1, 40, 60, 2, 128), (20, 20), (0, 0)),
+])
+def test_rope2d_apply_elementwise(mode, shape, win, shift):
+    (bits,) = synth.make_inputs("normal", 4001, shape, 1)
+    x64 = synth.bf16_bits_to_f64(bits)
+    tx = to_dev(bits)
+    Bn, H, W, nh, d = shape
+    phi = ro.angles(H, W, d, win, shift, 100.0, ro.POS_GRID if mode else ro.POS_WINDOW)
+    ty = B.aeris_rope2d_apply(tx, win, shift, 100.0, mode)
+    torch.cuda.synchronize()
+    assert pair_error_ok(to_f64(ty), ro.rotate(x64, phi))
+    # inverse, in place: back to the input within two roundings
+    tz = ty.clone()
+    B.aeris_rope2d_apply(tz, win, shift, 100.0, mode, inverse=True, y=tz)
+    torch.cuda.synchronize()
+    back = to_f64(tz)
+    assert pair_error_ok(back, ro.rotate(to_f64(ty), phi, inverse=True))
+    err2 = (back[..., 0::2] - x64[..., 0::2]) ** 2 + (back[..., 1::2] - x64[..., 1::2]) ** 2
+    len2 = x64[..., 0::2] ** 2 + x64[..., 1::2] ** 2
+    assert (err2 <= (2.0 ** -7) ** 2 * len2 + 1e-12).all()
+
+
+def test_rope2d_apply_other_base_and_origin_identity():
+    shape, win, shift = (1, 16, 16, 2, 32), (8, 8), (4, 4)
+    (bits,) = synth.make_inputs("normal", 4002, shape, 1)
+    x64 = synth.bf16_bits_to_f64(bits)
+    ty = B.aeris_rope2d_apply(to_dev(bits), win, shift, 10000.0, B.AERIS_ROPE_POS_GRID)
+    torch.cuda.synchronize()
+    phi = ro.angles(16, 16, 32, win, shift, 10000.0, ro.POS_GRID)
+    got = to_f64(ty)
+    assert pair_error_ok(got, ro.rotate(x64, phi))
+    np.testing.assert_array_equal(got[0, 0, 0], x64[0, 0, 0])     # position (0, 0): untouched
+
+
+def run_rope_case(shape, win, shift, mask, mode, base=100.0, kind="normal", seed=4100,
+                  outs=(B.AERIS_DT_F32, B.AERIS_DT_BF16)):
+    bits = synth.make_inputs(kind, seed, shape, 4)
+    q64, k64, v64, do64 = [synth.bf16_bits_to_f64(b) for b in bits]
+    tq, tk, tv, tdo = [to_dev(b) for b in bits]
+    pm = ro.POS_GRID if mode == B.AERIS_ROPE_POS_GRID else ro.POS_WINDOW
+    o_ref, lse_ref = ro.winattn_rope_fwd(q64, k64, v64, win, shift, mask, base, pm,
+                                         round_fn=round_bf16)
+    dq_ref, dk_ref, dv_ref = ro.winattn_rope_bwd(q64, k64, v64, do64, win, shift, mask, base, pm,
+                                                 round_fn=round_bf16)
+    # the embedding must matter in this case, or the test proves nothing
+    o_plain, _ = orc.winattn_fwd(q64, k64, v64, win, shift, mask)
+    assert np.linalg.norm(o_plain - o_ref) > 0.05 * np.linalg.norm(o_ref)
+    for out in outs:
+        bf = out == B.AERIS_DT_BF16
+        o, lse = B.aeris_winattn_rope_fwd(tq, tk, tv, win, shift, base, mode, mask, out_dtype=out)
+        torch.cuda.synchronize()
+        check("o", o, o_ref, bf)
+        assert np.abs(to_f64(lse) - lse_ref).max() <= LSE_ABS
+        dq, dk, dv = B.aeris_winattn_rope_bwd(tq, tk, tv, o, lse, tdo, win, shift, base, mode, mask,
+                                              out_dtype=out)
+        torch.cuda.synchronize()
+        check("dq", dq, dq_ref, bf)
+        check("dk", dk, dk_ref, bf)
+        check("dv", dv, dv_ref, bf)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("shape,win,shift,mask", [
+    ((1, 64, 128, 4, 32), (8, 8), (4, 4), B.AERIS_MASK_SWIN),
+    ((1, 36, 72, 2, 64), (12, 12), (6, 6), B.AERIS_MASK_LAT),
+    ((1, 40, 60, 2, 128), (20, 20), (10, 10), B.AERIS_MASK_NONE),
+    ((1, 40, 60, 2, 128), (20, 20), (0, 0), B.AERIS_MASK_NONE),
+])
+def test_rope_attention_fwd_bwd(mode, shape, win, shift, mask):
+    run_rope_case(shape, win, shift, mask, mode)
+
+
+def test_rope_attention_ragged_30x30_windows():
+    # T = 900: several resident tiles with a ragged tail; window-local positions
+    run_rope_case((1, 30, 60, 1, 128), (30, 30), (15, 15), B.AERIS_MASK_SWIN,
+                  B.AERIS_ROPE_POS_WINDOW, outs=(B.AERIS_DT_BF16,))
+
+
+def test_rope_attention_matches_two_step_composition():
+    """Rotating q and k with aeris_rope2d_apply and calling the plain forward gives the same
+    result as the fused call, bit for bit: both multiply the same bf16 operands."""
+    shape, win, shift, mask = (1, 36, 72, 2, 64), (12, 12), (6, 6), B.AERIS_MASK_SWIN
+    bits = synth.make_inputs("normal", 4200, shape, 3)
+    tq, tk, tv = [to_dev(b) for b in bits]
+    for mode in MODES:
+        o1, l1 = B.aeris_winattn_rope_fwd(tq, tk, tv, win, shift, 100.0, mode, mask)
+        qr = B.aeris_rope2d_apply(tq, win, shift, 100.0, mode)
+        kr = B.aeris_rope2d_apply(tk, win, shift, 100.0, mode)
+        o2, l2 = B.aeris_winattn_fwd(qr, kr, tv, win, shift, mask)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2) and torch.equal(l1, l2)
