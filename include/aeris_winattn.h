@@ -135,6 +135,29 @@ int aeris_winattn_bwd_stages(const aeris_winattn_params* p, const void* q, const
                              size_t workspace_bytes, void* hip_stream, unsigned stages);
 
 /*
+ * The same passes over a subset of the windows (SWiPe section: with window parallelism a
+ * rank holds a round-robin subset of the attention windows; the windows of one operation
+ * are independent, so a share is processed exactly as the whole).
+ *   windows   : DEVICE array of n_windows int32 window indices wy * (W_lon/win_w) + wx in
+ *               the shifted frame, 4-byte aligned, read-only; the same subset is
+ *               processed for every batch member and head.  1 <= n_windows <= number of
+ *               windows.  An index outside the grid of windows is skipped.  A window
+ *               listed twice is computed twice (same values written twice).
+ * Tensors keep the full-grid layout; only the tokens of the listed windows are read, and
+ * only their entries of o, lse, dq, dk, dv are written -- everything else is left
+ * untouched.  A workspace of aeris_winattn_bwd_workspace_bytes(p) bytes is always
+ * sufficient (the need shrinks in proportion to n_windows).
+ */
+int aeris_winattn_fwd_windows(const aeris_winattn_params* p, const int32_t* windows,
+                              int32_t n_windows, const void* q, const void* k, const void* v,
+                              void* o, float* lse, void* hip_stream);
+int aeris_winattn_bwd_windows(const aeris_winattn_params* p, const int32_t* windows,
+                              int32_t n_windows, const void* q, const void* k, const void* v,
+                              const void* o, const float* lse, const void* d_o, void* dq,
+                              void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                              void* hip_stream);
+
+/*
  * Rotary embedding of queries and keys (Model Architecture section: queries and keys
  * pass through an axial-frequency 2-D rotary position embedding before the dot-product
  * attention).  The paper gives no formula; this library takes the axial-frequency form

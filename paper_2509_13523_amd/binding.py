@@ -18,6 +18,7 @@ AERIS_ROPE_POS_WINDOW, AERIS_ROPE_POS_GRID = 0, 1
 EXPORTS = ("aeris_winattn_fwd", "aeris_winattn_bwd", "aeris_winattn_bwd_stages",
            "aeris_winattn_bwd_workspace_bytes",
            "aeris_winattn_validate", "aeris_winattn_strerror", "aeris_winattn_version",
+           "aeris_winattn_fwd_windows", "aeris_winattn_bwd_windows",
            "aeris_rope2d_apply", "aeris_winattn_rope_fwd_workspace_bytes",
            "aeris_winattn_rope_bwd_workspace_bytes", "aeris_winattn_rope_fwd",
            "aeris_winattn_rope_bwd")
@@ -75,6 +76,11 @@ def load():
     lib.aeris_winattn_strerror.restype = ctypes.c_char_p
     lib.aeris_winattn_version.argtypes = []
     lib.aeris_winattn_version.restype = ctypes.c_int
+    lib.aeris_winattn_fwd_windows.argtypes = [P, vp, ctypes.c_int32, vp, vp, vp, vp, vp, vp]
+    lib.aeris_winattn_fwd_windows.restype = ctypes.c_int
+    lib.aeris_winattn_bwd_windows.argtypes = [P, vp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, vp,
+                                              vp, vp, ctypes.c_size_t, vp]
+    lib.aeris_winattn_bwd_windows.restype = ctypes.c_int
     R = ctypes.POINTER(aeris_rope_params)
     lib.aeris_rope2d_apply.argtypes = [P, R, vp, vp, ctypes.c_int32, vp]
     lib.aeris_rope2d_apply.restype = ctypes.c_int
@@ -253,4 +259,41 @@ def aeris_winattn_rope_bwd(q, k, v, o, lse, d_o, win, shift, base, positions,
                                        _stream())
     if rc != 0:
         raise AerisError(rc, "aeris_winattn_rope_bwd")
+    return dq, dk, dv
+
+
+def aeris_winattn_fwd_windows(q, k, v, win, shift, windows, o, lse, mask=AERIS_MASK_NONE,
+                              scale=None, out_dtype=AERIS_DT_BF16):
+    """Forward over the listed windows only.  windows: int32 device tensor of indices
+    wy * (W/win_w) + wx; o and lse are caller-provided and written only inside those windows."""
+    import torch
+    assert windows.is_cuda and windows.dtype == torch.int32 and windows.is_contiguous()
+    for t in (q, k, v):
+        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.shape == q.shape
+    p = make_params(q.shape, win, shift, mask, scale, out_dtype)
+    rc = load().aeris_winattn_fwd_windows(ctypes.byref(p), windows.data_ptr(), windows.numel(),
+                                          q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                          lse.data_ptr(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_winattn_fwd_windows")
+    return o, lse
+
+
+def aeris_winattn_bwd_windows(q, k, v, o, lse, d_o, win, shift, windows, dq, dk, dv,
+                              mask=AERIS_MASK_NONE, scale=None, out_dtype=AERIS_DT_BF16,
+                              workspace=None):
+    """Backward over the listed windows only; dq, dk, dv are written only inside them."""
+    import torch
+    assert windows.is_cuda and windows.dtype == torch.int32 and windows.is_contiguous()
+    p = make_params(q.shape, win, shift, mask, scale, out_dtype)
+    if workspace is None:
+        workspace = torch.empty(aeris_winattn_bwd_workspace_bytes(p), dtype=torch.uint8,
+                                device=q.device)
+    rc = load().aeris_winattn_bwd_windows(ctypes.byref(p), windows.data_ptr(), windows.numel(),
+                                          q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                          lse.data_ptr(), d_o.data_ptr(), dq.data_ptr(),
+                                          dk.data_ptr(), dv.data_ptr(), workspace.data_ptr(),
+                                          workspace.numel(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_winattn_bwd_windows")
     return dq, dk, dv

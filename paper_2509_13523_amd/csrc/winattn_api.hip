@@ -59,7 +59,9 @@ aeris::KParams derive(const aeris_winattn_params* p, const Strides& s) {
   k.nWx = p->W_lon / p->win_w;
   k.T = p->win_h * p->win_w;
   k.n_tiles = (k.T + aeris::kResident - 1) / aeris::kResident;
-  k.n_pairs = k.B * k.nWy * k.nWx * k.nh;
+  k.n_win = k.nWy * k.nWx;
+  k.win_list = nullptr;
+  k.n_pairs = k.B * k.n_win * k.nh;
   k.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.f / sqrtf((float)p->head_dim);
   k.scale_log2 = k.scale * 1.4426950408889634f;
   k.qkv_tok = k.q_tok = k.k_tok = s.qkv_tok;
@@ -111,6 +113,60 @@ int aeris_winattn_fwd(const aeris_winattn_params* p, const void* q, const void* 
   const aeris::KParams kp = derive(p, s);
   if (aeris::launch_fwd(kp, p->head_dim, p->out_dtype == AERIS_DT_F32, q, k, v, o, lse,
                         static_cast<hipStream_t>(hip_stream)) != 0)
+    return AERIS_ERR_HIP_LAUNCH;
+  return AERIS_OK;
+}
+
+// Restricts derived parameters to a list of windows.
+int restrict_windows(aeris::KParams* k, const int32_t* windows, int32_t n_windows) {
+  if (!windows) return AERIS_ERR_NULL_POINTER;
+  if (n_windows <= 0 || n_windows > k->nWy * k->nWx) return AERIS_ERR_INVALID_SHAPE;
+  if (reinterpret_cast<uintptr_t>(windows) & 3) return AERIS_ERR_MISALIGNED;
+  k->win_list = windows;
+  k->n_win = n_windows;
+  k->n_pairs = k->B * k->n_win * k->nh;
+  return AERIS_OK;
+}
+
+int aeris_winattn_fwd_windows(const aeris_winattn_params* p, const int32_t* windows,
+                              int32_t n_windows, const void* q, const void* k, const void* v,
+                              void* o, float* lse, void* hip_stream) {
+  Strides s;
+  int rc = resolve(p, &s);
+  if (rc != AERIS_OK) return rc;
+  if (!q || !k || !v || !o || !lse) return AERIS_ERR_NULL_POINTER;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse))
+    return AERIS_ERR_MISALIGNED;
+  aeris::KParams kp = derive(p, s);
+  rc = restrict_windows(&kp, windows, n_windows);
+  if (rc != AERIS_OK) return rc;
+  if (aeris::launch_fwd(kp, p->head_dim, p->out_dtype == AERIS_DT_F32, q, k, v, o, lse,
+                        static_cast<hipStream_t>(hip_stream)) != 0)
+    return AERIS_ERR_HIP_LAUNCH;
+  return AERIS_OK;
+}
+
+int aeris_winattn_bwd_windows(const aeris_winattn_params* p, const int32_t* windows,
+                              int32_t n_windows, const void* q, const void* k, const void* v,
+                              const void* o, const float* lse, const void* d_o, void* dq, void* dk,
+                              void* dv, void* workspace, size_t workspace_bytes,
+                              void* hip_stream) {
+  Strides s;
+  int rc = resolve(p, &s);
+  if (rc != AERIS_OK) return rc;
+  if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !workspace)
+    return AERIS_ERR_NULL_POINTER;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) ||
+      misaligned(d_o) || misaligned(dq) || misaligned(dk) || misaligned(dv) ||
+      misaligned(workspace))
+    return AERIS_ERR_MISALIGNED;
+  aeris::KParams kp = derive(p, s);
+  rc = restrict_windows(&kp, windows, n_windows);
+  if (rc != AERIS_OK) return rc;
+  if (workspace_bytes < aeris::bwd_workspace_bytes(kp)) return AERIS_ERR_WORKSPACE_TOO_SMALL;
+  if (aeris::launch_bwd(kp, p->head_dim, p->out_dtype == AERIS_DT_F32, q, k, v, o, lse, d_o, dq,
+                        dk, dv, static_cast<float*>(workspace),
+                        static_cast<hipStream_t>(hip_stream), AERIS_BWD_ALL) != 0)
     return AERIS_ERR_HIP_LAUNCH;
   return AERIS_OK;
 }

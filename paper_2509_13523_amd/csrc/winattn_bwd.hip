@@ -65,7 +65,15 @@ __global__ __launch_bounds__(kThreads) void winattn_delta_kernel(
   }
   if (t >= p.T) return;   // whole token groups leave together (kChunks divides 64)
   Window win;
-  win.init(p, pair);
+  if (!win.init(p, pair)) {
+    // a skipped window still gets finite statistics: the streamed tiles of the pair before
+    // it read up to 63 entries past their own end
+    if (chunk == 0) {
+      delta[(long long)pair * p.T + t] = 0.f;
+      lse2[(long long)pair * p.T + t] = 0.f;
+    }
+    return;
+  }
   const long long plane = (long long)p.H * p.W;
   const int g = win.grid_index(p, t);
   const long long off = ((long long)win.b * plane + g) * p.o_tok + (long long)win.head * p.o_head +
@@ -109,7 +117,7 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
   if (!block_to_work(p, pair, qt)) return;
 
   Window win;
-  win.init(p, pair);
+  if (!win.init(p, pair)) return;
   build_token_table(p, win, tok_grid);
   __syncthreads();
 
@@ -277,7 +285,7 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 1 : 2) void winattn_dkdv_kerne
   if (!block_to_work(p, pair, kt)) return;
 
   Window win;
-  win.init(p, pair);
+  if (!win.init(p, pair)) return;
   build_token_table(p, win, tok_grid);
   __syncthreads();
 

@@ -39,9 +39,11 @@ struct KParams {
   int ws_h, ws_w, s_h, s_w;
   int mask;            // AERIS_MASK_*
   int nWy, nWx;        // windows along latitude / longitude
+  int n_win;           // windows processed per batch member: nWy*nWx, or the length of win_list
+  const int* win_list; // device array of n_win window indices wy*nWx + wx, or null = all windows
   int T;               // tokens per window
   int n_tiles;         // resident-side tiles per window = ceil(T / kResident)
-  int n_pairs;         // B * nWy * nWx * nh
+  int n_pairs;         // B * n_win * nh
   float scale;         // softmax scale
   float scale_log2;    // scale * log2(e)
   long long qkv_tok, qkv_head;  // element strides of v and of dq, dk, dv
@@ -92,13 +94,17 @@ struct Window {
   int wc0, wc1;           // columns in the left / right region
   int s01, s10, s11, T;   // enumeration start of regions (0,1), (1,0), (1,1)
 
-  __device__ __forceinline__ void init(const KParams& p, int pair) {
+  // False (uniformly for the workgroup) if a listed window index is out of range: the
+  // caller then leaves before touching memory.
+  __device__ __forceinline__ bool init(const KParams& p, int pair) {
     head = pair % p.nh;
-    int w = pair / p.nh;
-    wx = w % p.nWx;
-    w /= p.nWx;
-    wy = w % p.nWy;
-    b = w / p.nWy;
+    const int w = pair / p.nh;
+    b = w / p.n_win;
+    int idx = w - b * p.n_win;
+    if (p.win_list) idx = p.win_list[idx];
+    if ((unsigned)idx >= (unsigned)(p.nWy * p.nWx)) return false;
+    wy = idx / p.nWx;
+    wx = idx - wy * p.nWx;
     const bool lat_seam = p.mask != 0 && wy == p.nWy - 1 && p.s_h > 0;
     const bool lon_seam = p.mask == 2 && wx == p.nWx - 1 && p.s_w > 0;
     split_r = lat_seam ? p.ws_h - p.s_h : p.ws_h;
@@ -110,6 +116,7 @@ struct Window {
     s10 = s01 + hr0 * wc1;
     s11 = s10 + hr1 * wc0;
     T = p.T;
+    return true;
   }
   // Visible key range of token t.
   __device__ __forceinline__ void range(int t, int& lo, int& hi) const {

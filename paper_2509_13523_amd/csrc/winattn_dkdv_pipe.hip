@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
   if (!block_to_work(p, pair, kt)) return;
 
   Window win;
-  win.init(p, pair);
+  if (!win.init(p, pair)) return;
   build_token_table(p, win, tok_grid);
   __syncthreads();
 

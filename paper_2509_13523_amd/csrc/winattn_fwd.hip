@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
   if (!block_to_work(p, pair, qt)) return;
 
   Window win;
-  win.init(p, pair);
+  if (!win.init(p, pair)) return;
   build_token_table(p, win, tok_grid);
   __syncthreads();
 

@@ -98,3 +98,22 @@ def test_rope_arguments_rejected_before_launch():
                                       tensor - 1, None) == -8
     assert lib.aeris_winattn_rope_bwd(ctypes.byref(p), ctypes.byref(r), a, a, a, a, a, a, a, a, a,
                                       a, 2 * tensor, None) == -8
+
+
+def test_window_list_arguments_rejected_before_launch():
+    lib = B.load()
+    p = B.make_params((1, 64, 128, 4, 32), (8, 8), (4, 4))      # 8 x 16 = 128 windows
+    buf = (ctypes.c_char * 64)()
+    a = ctypes.addressof(buf)
+    a += (-a) % 16
+    fwd = lambda lst, n: lib.aeris_winattn_fwd_windows(ctypes.byref(p), lst, n, a, a, a, a, a, None)
+    assert fwd(None, 4) == -1
+    assert fwd(a, 0) == -2
+    assert fwd(a, -3) == -2
+    assert fwd(a, 129) == -2
+    assert fwd(a + 2, 4) == -7
+    assert lib.aeris_winattn_bwd_windows(ctypes.byref(p), None, 4, a, a, a, a, a, a, a, a, a, a,
+                                         1 << 30, None) == -1
+    # four of 128 windows need 1/32 of the full workspace (plus padding): 16 bytes are too few
+    assert lib.aeris_winattn_bwd_windows(ctypes.byref(p), a, 4, a, a, a, a, a, a, a, a, a, a,
+                                         16, None) == -8
