@@ -175,71 +175,152 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
 
-  auto sub_block = [&](auto off, int sub_lo) __attribute__((always_inline)) {
+  // Schedule of one 32-key block, as in the forward kernel (LDS offsets are compile-time
+  // constants):
+  //   logits phase   2*D/16 products S^T = K Q^T, dP^T = V dO^T.  Their operands pass through
+  //                  a window of kWin contraction blocks: the first kWin were fetched during
+  //                  the previous block's output phase, block kk + kWin is fetched right after
+  //                  the products of block kk; copies of the next tile are issued in between;
+  //   vector phase   K^T operands of this block are fetched (transposing reads), then
+  //                  P = exp2(S - LSE), dS = P o (dP - delta), rounded to bf16;
+  //   output phase   D/16 products dQ^T += K^T dS^T, with the first kWin operand blocks of the
+  //                  NEXT block fetched and further copies issued in between.
+  constexpr int kNK = D / 16;
+  constexpr int kWin = kNK < 4 ? kNK : 4;
+  constexpr int kF = Tl::kFillPerWave;
+  bf16x8 ka[kNK], va[kNK], kta[D / 32][2];
+  f32x16 sacc, dpacc;
+  union { u32x4 u; bf16x8 h; } dsb[2];
+
+  auto fetch_rows = [&](auto off, int kk) __attribute__((always_inline)) {
     constexpr uint32_t kOff = decltype(off)::value;
-    if (rg.skip(sub_lo)) return;
-    // operand reads first, products after: LDS latency hides behind the MFMA pipeline
-    bf16x8 ka[D / 16], va[D / 16], kta[D / 32][2];
+    ka[kk] = Tl::read_rm(la.rm[kk] + kOff);
+    va[kk] = Tl::read_rm(la.rm[kk] + kOff + Tl::kBytes);
+  };
+  auto fetch_first = [&](auto off) __attribute__((always_inline)) {
 #pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) {
-      ka[kk] = Tl::read_rm(la.rm[kk] + kOff);
-      va[kk] = Tl::read_rm(la.rm[kk] + kOff + Tl::kBytes);
+    for (int kk = 0; kk < kWin; ++kk) fetch_rows(off, kk);
+  };
+  // en: non-zero if the copies are wanted (wave-uniform)
+  auto logits_phase = [&](auto off, auto with_fill, const typename Tl::Filler& fill,
+                          uint32_t fill_tile, uint32_t en) __attribute__((always_inline)) {
+    constexpr bool kFill = decltype(with_fill)::value != 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
+    sched_fence();
+#pragma unroll
+    for (int kk = 0; kk < kNK; ++kk) {
+      sacc = mfma32(ka[kk], qreg[kk], sacc);
+      dpacc = mfma32(va[kk], doreg[kk], dpacc);
+      if (kk + kWin < kNK) fetch_rows(off, kk + kWin);
+      if (kFill && (kk * kF) % kNK < kF && (kk * kF) / kNK < kF)
+        fill.issue_one_if((kk * kF) / kNK, fill_tile, rows, en);
+      sched_fence();
     }
+  };
+  auto vector_phase = [&](auto off, int sub_lo) __attribute__((always_inline)) {
+    constexpr uint32_t kOff = decltype(off)::value;
 #pragma unroll
     for (int cb = 0; cb < D / 32; ++cb)
 #pragma unroll
       for (int c = 0; c < 2; ++c)
         kta[cb][c] = Tl::read_tr(la.tr[cb][0] + kOff + c * Tl::kGroupBytes,
                                  la.tr[cb][1] + kOff + c * Tl::kGroupBytes);
-    f32x16 s, dp;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
-#pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) {
-      s = mfma32(ka[kk], qreg[kk], s);
-      dp = mfma32(va[kk], doreg[kk], dp);
-    }
     if (!rg.mask_free(sub_lo)) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int kidx = sub_lo + acc_row(i, g);
-        if (kidx < lo_q || kidx >= hi_q) s[i] = -INFINITY;
+        if (kidx < lo_q || kidx >= hi_q) sacc[i] = -INFINITY;
       }
     }
     float ds[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], p.scale_log2, -lse2));
-      ds[i] = pr * (dp[i] - delta_q);
+      const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], p.scale_log2, -lse2));
+      ds[i] = pr * (dpacc[i] - delta_q);
     }
-    union { u32x4 u; bf16x8 h; } dsb[2];
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
       for (int e = 0; e < 4; ++e) dsb[c].u[e] = pack_bf16(ds[8 * c + 2 * e], ds[8 * c + 2 * e + 1]);
+  };
+  auto output_phase = [&](auto next_off, auto with_fill, const typename Tl::Filler& fill,
+                          uint32_t fill_tile, uint32_t en) __attribute__((always_inline)) {
+    constexpr bool kFill = decltype(with_fill)::value != 0;
+    sched_fence();
 #pragma unroll
-    for (int cb = 0; cb < D / 32; ++cb)
+    for (int j = 0; j < kNK; ++j) {
+      const int c = j / (D / 32), cb = j % (D / 32);
+      acc[cb] = mfma32(kta[cb][c], dsb[c].h, acc[cb]);
+      if (j % 2 == 0 && j / 2 < kWin) fetch_rows(next_off, j / 2);
+      if (kFill && (j & 1) && (j >> 1) < kF) fill.issue_one_if(j >> 1, fill_tile, rows, en);
+      sched_fence();
+    }
+    if (kWin > (kNK + 1) / 2) {   // narrow heads: the output phase is shorter than the window
 #pragma unroll
-      for (int c = 0; c < 2; ++c) acc[cb] = mfma32(kta[cb][c], dsb[c].h, acc[cb]);
+      for (int kk = (kNK + 1) / 2; kk < kWin; ++kk) fetch_rows(next_off, kk);
+    }
   };
 
+  // Tile kt lives in buffer (kt - kt_begin) & 1.  While it is processed, the V copies of tile
+  // kt+1 are issued (its K copies were issued during tile kt-1); a barrier after the vector
+  // phase of the second block publishes tile kt+1 and retires the readers of tile kt, after
+  // which the K copies of tile kt+2 go into this tile's buffer.
+  const int kt_last = kt_end - 1;
+  auto prepare_after_next = [&](int kt) __attribute__((always_inline)) {
+    rows.prepare((kt + 2 < kt_last ? kt + 2 : kt_last) * kStream);
+  };
   auto tile_step = [&](auto parity, int kt) __attribute__((always_inline)) {
     constexpr uint32_t kP = decltype(parity)::value;
+    constexpr uint32_t kCur = kP * kBuf, kNext = (1 - kP) * kBuf;
+    const uint32_t has1 = kt + 1 < kt_end, has2 = kt + 2 < kt_end;
+    logits_phase(Const<kCur>{}, Const<1>{}, vfill, tiles + kNext + Tl::kBytes, has1);
+    prepare_after_next(kt);
+    vector_phase(Const<kCur>{}, kt * kStream);
+    output_phase(Const<kCur + Tl::kSubBytes>{}, Const<0>{}, kfill, 0, 0);
+    logits_phase(Const<kCur + Tl::kSubBytes>{}, Const<0>{}, vfill, 0, 0);
+    vector_phase(Const<kCur + Tl::kSubBytes>{}, kt * kStream + 32);
     wait_async_loads();
     __syncthreads();
-    if (kt + 1 < kt_end) {     // table entries were read one tile ago
-      kfill.issue(tiles + (1 - kP) * kBuf, rows);
-      vfill.issue(tiles + (1 - kP) * kBuf + Tl::kBytes, rows);
-      if (kt + 2 < kt_end) rows.prepare((kt + 2) * kStream);
-    }
-    if (!rg.wave_active) return;
-    sub_block(Const<kP * kBuf>{}, kt * kStream);
-    sub_block(Const<kP * kBuf + Tl::kSubBytes>{}, kt * kStream + 32);
+    output_phase(Const<kNext>{}, Const<1>{}, kfill, tiles + kCur, has2);
   };
-  for (int kt = kt_begin; kt < kt_end; kt += 2) {
-    tile_step(Const<0>{}, kt);
-    if (kt + 1 < kt_end) tile_step(Const<1>{}, kt + 1);
+  auto idle_step = [&](int kt) __attribute__((always_inline)) {
+    const uint32_t cur = tiles + ((kt - kt_begin) & 1) * kBuf, next = tiles + kBuf - (cur - tiles);
+    vfill.issue_if(next + Tl::kBytes, rows, kt + 1 < kt_end);
+    prepare_after_next(kt);
+    wait_async_loads();
+    __syncthreads();
+    kfill.issue_if(cur, rows, kt + 2 < kt_end);
+  };
+
+  // This wave's tiles: [wt_lo, wt_hi) inside the workgroup's [kt_begin, kt_end).
+  const int wt_lo = rg.wave_active ? rg.w_lo / kStream : kt_end;
+  const int wt_hi = rg.wave_active ? (rg.w_hi + kStream - 1) / kStream : kt_end;
+
+  wait_async_loads();
+  __syncthreads();
+  kfill.issue_if(tiles + kBuf, rows, kt_begin + 1 < kt_end);
+  int kt = kt_begin;
+  for (; kt < wt_lo; ++kt) idle_step(kt);
+  if (kt < wt_hi) {
+    if ((kt - kt_begin) & 1) {
+      fetch_first(Const<kBuf>{});
+      tile_step(Const<1>{}, kt);
+      ++kt;
+    } else {
+      fetch_first(Const<0>{});
+    }
+    for (; kt + 1 < wt_hi; kt += 2) {
+      tile_step(Const<0>{}, kt);
+      tile_step(Const<1>{}, kt + 1);
+    }
+    if (kt < wt_hi) {
+      tile_step(Const<0>{}, kt);
+      ++kt;
+    }
   }
+  for (; kt < kt_end; ++kt) idle_step(kt);
+  wait_async_loads();
 
   if (!rg.valid) return;
   OutT* row = dq + qkv_base + (long long)q_grid * p.qkv_tok;
