@@ -12,11 +12,15 @@ SOURCES = ["winattn_api.hip", "winattn_fwd.hip", "winattn_bwd.hip", "winattn_dkd
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", INCLUDE, "-I", CSRC]
+# Per-file additions.  The pipelined dK/dV kernel wants MFMA results in ordinary VGPRs (its
+# vector stage reads the logits straight from them); it pins its gradient accumulators to
+# accumulation registers itself.
+EXTRA = {"winattn_dkdv_pipe.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _compile(src):
     obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-    cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = ["hipcc", *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)

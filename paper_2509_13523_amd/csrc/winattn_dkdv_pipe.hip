@@ -23,6 +23,15 @@ __device__ unsigned long long aeris_stage_ticks[16];
 
 namespace aeris {
 
+// c += a b with c pinned to accumulation registers.  This file is compiled with MFMA results
+// in ordinary VGPRs by default, so that the vector stage reads the logits where the products
+// deliver them; the 2 x 128 gradient accumulators, which only MFMAs touch inside the loop,
+// are kept in accumulation registers by this statement.  Products on one accumulator are two
+// MFMAs apart, and the epilogue waits out the MFMA latency before it reads them.
+__device__ __forceinline__ void mfma32_acc(bf16x8 a, bf16x8 b, f32x16& c) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+
 template <int D>
 constexpr size_t dkdv_pipe_smem_bytes(int T) {
   return table_bytes(T) + 3 * (2 * Tile<D>::kBytes + 2 * kStream * 4);
@@ -114,7 +123,9 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) { dkacc[cb][i] = 0.f; dvacc[cb][i] = 0.f; }
 
-  f32x16 s, dp;                                   // logits of the block stage B consumes next
+  // Logits of the block stage B consumes next.  Two sets: while stage B reads one, stage A
+  // of the following block accumulates into the other (no copies between stages).
+  f32x16 s0, dp0, s1, dp1;
   union Packed { u32x4 u; bf16x8 h; };
   Packed pb[2], dsb[2];                           // P, dS of the block stage C consumes
 
@@ -135,16 +146,17 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
 #pragma unroll
     for (int i = 0; i < kNA; ++i) op[i] = a_operand(i, sub);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+    for (int i = 0; i < 16; ++i) { s0[i] = 0.f; dp0[i] = 0.f; }
 #pragma unroll
     for (int i = 0; i < kNA; ++i) {
-      if (i & 1) dp = mfma32(op[i], vreg[i >> 1], dp);
-      else s = mfma32(op[i], kreg[i >> 1], s);
+      if (i & 1) dp0 = mfma32(op[i], vreg[i >> 1], dp0);
+      else s0 = mfma32(op[i], kreg[i >> 1], s0);
     }
   };
 
   // Vector work for logit e of the current block (statistics l, d of its query row).
-  auto b_element = [&](auto masked, int e, float l, float d, int sub_lo, float* pr, float* ds) __attribute__((always_inline)) {
+  auto b_element = [&](auto masked, const f32x16& s, const f32x16& dp, int e, float l, float d,
+                       int sub_lo, float* pr, float* ds) __attribute__((always_inline)) {
     float se = s[e];
     if (decltype(masked)::value) {
       const int qidx = sub_lo + acc_row(e, g);
@@ -154,13 +166,27 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
     ds[e] = pr[e] * (dp[e] - d);
   };
 
+  // piece i (0 .. 2*kFillPerWave) of a tile fill whose table entries were prepared
+  // earlier: Q rows, dO rows, statistics
+  auto fill_piece = [&](int i, uint32_t buf, int t0) __attribute__((always_inline)) {
+    if (i < Tl::kFillPerWave) qfill.issue_one(i, buf, rows);
+    else if (i < 2 * Tl::kFillPerWave) dofill.issue_one(i - Tl::kFillPerWave, buf + Tl::kBytes, rows);
+    else if (wave < 2) async_copy4(stat_src + t0, buf + kStat + wave * (kStream * 4));
+  };
+
   // Stage B(cur) interleaved with stage A(next) when kNext, else B alone.
   //   nsub: LDS offset of the next block's rows relative to `rm`;
   //   csub_stat: offset of the current block's statistics relative to `st`.
-  auto stage_ab = [&](auto has_next, auto masked, uint32_t nsub, uint32_t csub_stat, int sub_lo) __attribute__((always_inline)) {
+  //   s, dp: logits of the current block; sn, dpn: receive those of the next one.
+  //   do_fill (wave-uniform): the pieces of a tile fill are dropped into the first slots, one
+  //   per slot (issued as a burst they stall the wave until the memory pipeline drains).  They
+  //   ride here rather than in stage C because stage C keeps the LDS busier (transposing reads
+  //   run at half the rate of row reads) and the copies land in the LDS too.
+  auto stage_ab = [&](auto has_next, auto masked, const f32x16& s, const f32x16& dp, f32x16& sn,
+                      f32x16& dpn, uint32_t nsub, uint32_t csub_stat, int sub_lo, bool do_fill,
+                      uint32_t fill_buf, int fill_t0) __attribute__((always_inline)) {
     constexpr bool kNext = decltype(has_next)::value;
     constexpr int kAhead = 3;                     // LDS reads run this many MFMAs ahead
-    f32x16 sn, dpn;
     bf16x8 op[kNA];
     f32x4 l4[4], d4[4];
     float pr[16], ds[16];
@@ -187,7 +213,8 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
           else sn = mfma32(op[i], kreg[i >> 1], sn);
         }
       }
-      b_element(masked, e, l4[e >> 2][e & 3], d4[e >> 2][e & 3], sub_lo, pr, ds);
+      if (e <= 2 * Tl::kFillPerWave && do_fill) fill_piece(e, fill_buf, fill_t0);
+      b_element(masked, s, dp, e, l4[e >> 2][e & 3], d4[e >> 2][e & 3], sub_lo, pr, ds);
       if (e & 1) {
         const int c = e >> 3, w = (e >> 1) & 3;
         pb[c].u[w] = pack_bf16(pr[e - 1], pr[e]);
@@ -195,24 +222,10 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (kNext) {
-      s = sn;
-      dp = dpn;
-    }
   };
 
-  // piece i (0 .. 2*kFillPerWave) of a tile fill whose table entries were prepared
-  // earlier: Q rows, dO rows, statistics
-  auto fill_piece = [&](int i, uint32_t buf, int t0) __attribute__((always_inline)) {
-    if (i < Tl::kFillPerWave) qfill.issue_one(i, buf, rows);
-    else if (i < 2 * Tl::kFillPerWave) dofill.issue_one(i - Tl::kFillPerWave, buf + Tl::kBytes, rows);
-    else if (wave < 2) async_copy4(stat_src + t0, buf + kStat + wave * (kStream * 4));
-  };
-
-  // Stage C: the 16 accumulating products of the current block.  When do_fill
-  // (wave-uniform), the pieces of a tile fill are dropped between the MFMAs one at a
-  // time: issued as a burst they stall the wave until the memory pipeline drains.
-  auto stage_c = [&](uint32_t sub, bool do_fill, uint32_t fill_buf, int fill_t0) __attribute__((always_inline)) {
+  // Stage C: the 16 accumulating products of the current block.
+  auto stage_c = [&](uint32_t sub) __attribute__((always_inline)) {
     constexpr int kAhead = 3;
     bf16x8 op[kNC];
 #pragma unroll
@@ -221,21 +234,22 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
     for (int i = 0; i < kNC; ++i) {
       if (i + kAhead < kNC) op[i + kAhead] = c_operand(i + kAhead, sub);
       const int cb = i >> 2, c = (i >> 1) & 1;
-      if (i & 1) dkacc[cb] = mfma32(op[i], dsb[c].h, dkacc[cb]);
-      else dvacc[cb] = mfma32(op[i], pb[c].h, dvacc[cb]);
-      if (i <= 2 * Tl::kFillPerWave && do_fill) fill_piece(i, fill_buf, fill_t0);
+      if (i & 1) mfma32_acc(op[i], dsb[c].h, dkacc[cb]);
+      else mfma32_acc(op[i], pb[c].h, dvacc[cb]);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  auto run_ab = [&](bool has_next, uint32_t nsub, uint32_t csub_stat, int sub_lo) __attribute__((always_inline)) {
+  auto run_ab = [&](bool has_next, const f32x16& s, const f32x16& dp, f32x16& sn, f32x16& dpn,
+                    uint32_t nsub, uint32_t csub_stat, int sub_lo, bool do_fill, uint32_t fill_buf,
+                    int fill_t0) __attribute__((always_inline)) {
     const bool mf = rg.mask_free(sub_lo);
     if (has_next) {
-      if (mf) stage_ab(std::true_type{}, std::false_type{}, nsub, csub_stat, sub_lo);
-      else stage_ab(std::true_type{}, std::true_type{}, nsub, csub_stat, sub_lo);
+      if (mf) stage_ab(std::true_type{}, std::false_type{}, s, dp, sn, dpn, nsub, csub_stat, sub_lo, do_fill, fill_buf, fill_t0);
+      else stage_ab(std::true_type{}, std::true_type{}, s, dp, sn, dpn, nsub, csub_stat, sub_lo, do_fill, fill_buf, fill_t0);
     } else {
-      if (mf) stage_ab(std::false_type{}, std::false_type{}, nsub, csub_stat, sub_lo);
-      else stage_ab(std::false_type{}, std::true_type{}, nsub, csub_stat, sub_lo);
+      if (mf) stage_ab(std::false_type{}, std::false_type{}, s, dp, sn, dpn, nsub, csub_stat, sub_lo, do_fill, fill_buf, fill_t0);
+      else stage_ab(std::false_type{}, std::true_type{}, s, dp, sn, dpn, nsub, csub_stat, sub_lo, do_fill, fill_buf, fill_t0);
     }
   };
 
@@ -252,12 +266,13 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
   AERIS_TICK_DECL
   for (int qt = qt_begin; qt < qt_end; ++qt) {
     const bool more = qt + 1 < qt_end;
+    if (qt + 2 < qt_end) rows.prepare((qt + 2) * kStream);   // table entries of tile qt+2: used two stages later
     AERIS_TICK(7)
     // first half: A(tile qt, block 1) with B(tile qt, block 0); then C(block 0)
     if (rg.wave_active) {
-      run_ab(true, Tl::kSubBytes, 0, qt * kStream);
+      run_ab(true, s0, dp0, s1, dp1, Tl::kSubBytes, 0, qt * kStream, false, 0, 0);
       AERIS_TICK(0)
-      stage_c(0, false, 0, 0);
+      stage_c(0);
       AERIS_TICK(1)
     }
     // tile qt+1 must be visible before stage A touches it; this barrier also
@@ -275,13 +290,12 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
 #pragma unroll
       for (int kk = 0; kk < kNK; ++kk) la.rm[kk] += step;
     }
-    if (do_fill) rows.prepare(fill_t0);   // table entries of tile qt+2: used a whole stage later
     AERIS_TICK(2)
     // second half: A(tile qt+1, block 0) with B(tile qt, block 1); then C(block 1)
     if (rg.wave_active) {
-      run_ab(more, 0, 32 * 4, qt * kStream + 32);
+      run_ab(more, s1, dp1, s0, dp0, 0, 32 * 4, qt * kStream + 32, do_fill, fill_buf, fill_t0);
       AERIS_TICK(3)
-      stage_c(Tl::kSubBytes, do_fill, fill_buf, fill_t0);   // after the barrier: buffer is free
+      stage_c(Tl::kSubBytes);
       AERIS_TICK(4)
     } else if (do_fill) {        // waves without real keys still move their share of the tile
 #pragma unroll
@@ -299,6 +313,7 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
     }
   }
   AERIS_TICK_FLUSH(aeris_stage_ticks)
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // last accumulating MFMAs retire
 
   if (!rg.valid) return;
   OutT* dkrow = dk + qkv_base + (long long)k_grid * p.qkv_tok;
