@@ -46,7 +46,7 @@ WORKLOADS = {
 # HBM traffic per launch, bytes, from two rocprofv3 --pmc runs of this file (FETCH_SIZE, then
 # WRITE_SIZE, each scaled by what the same counter reads for the --calibrate-copy kernels:
 # factors 2.000 and 1.000); profiles/c5_kernels_and_counters.txt has the commands and numbers.
-MEASURED_TRAFFIC = {("c5", "fwd"): 78.0e9, ("c5", "dq"): 88.7e9, ("c5", "dkdv"): 112.3e9}
+MEASURED_TRAFFIC = {("c5", "fwd"): 71.6e9, ("c5", "dq"): 88.8e9, ("c5", "dkdv"): 111.9e9}
 
 
 def unmasked_pairs(H, W, win, shift, mask):
@@ -68,7 +68,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-pairs", type=int, default=8)
+    ap.add_argument("--cpu-pairs", type=int, default=64)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="end with three 1 GiB read + 1 GiB write elementwise kernels "
                          "(the last three dispatches), to scale rocprofv3 FETCH_SIZE/WRITE_SIZE")
