@@ -41,6 +41,10 @@ WORKLOADS = {
     "c3": dict(shape=(1, 720, 1440, 16, 64), win=(60, 60), layers=[(30, 30)], mask=2,
                kind="normal", sigmas=None, bwd=False, seed=3000,
                name="720x1440 grid, 16 heads x 64, 60x60 windows, shift 30, forward only"),
+    # the 6-hourly model's windows (Model Architecture section): T = 900, ragged tiles on both sides
+    "w30": dict(shape=(1, 720, 1440, 16, 128), win=(30, 30), layers=[(0, 0), (15, 15)], mask=2,
+                kind="blend", sigmas=None, bwd=True, seed=6000,
+                name="720x1440 grid, 16 heads x 128, 30x30 windows, shift 0/15, SWIN mask"),
 }
 
 # HBM traffic per launch, bytes, from two rocprofv3 --pmc runs of this file (FETCH_SIZE, then

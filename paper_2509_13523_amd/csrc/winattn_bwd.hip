@@ -570,9 +570,9 @@ static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const v
                        static_cast<OutT*>(dq));
     if (hipGetLastError() != hipSuccess) return -1;
   }
-  if ((stages & 4u) && D == 128) {
-    if (launch_dkdv_pipe128(kp, std::is_same<OutT, float>::value, q, k, v, d_o, delta, lse2, dk,
-                            dv, stream) != 0)
+  if constexpr (D == 128) {   // software-pipelined kernel; the generic one is not built for it
+    if ((stages & 4u) && launch_dkdv_pipe128(kp, std::is_same<OutT, float>::value, q, k, v, d_o,
+                                             delta, lse2, dk, dv, stream) != 0)
       return -1;
   } else if (stages & 4u) {
     const size_t smem = dkdv_smem_bytes<D>(kp.T);
