@@ -127,3 +127,34 @@ def test_rope_attention_matches_two_step_composition():
         o2, l2 = B.aeris_winattn_fwd(qr, kr, tv, win, shift, mask)
         torch.cuda.synchronize()
         assert torch.equal(o1, o2) and torch.equal(l1, l2)
+
+
+def test_rope_band_share_full_size_sampled():
+    """Config-4 launch shape (48 windows of 60x60, 24 heads x 128) with grid positions, whose
+    longitude positions reach 1439: sampled (window, head) pairs against the oracle."""
+    shape, win, shift, mask = (1, 120, 1440, 24, 128), (60, 60), (30, 30), B.AERIS_MASK_SWIN
+    Bn, H, W, nh, d = shape
+    base, mode = 100.0, B.AERIS_ROPE_POS_GRID
+    tq, tk, tv, tdo = synth.make_inputs_device("blend", 4301, shape, 4)
+    o, lse = B.aeris_winattn_rope_fwd(tq, tk, tv, win, shift, base, mode, mask,
+                                      out_dtype=B.AERIS_DT_F32)
+    dq, dk, dv = B.aeris_winattn_rope_bwd(tq, tk, tv, o, lse, tdo, win, shift, base, mode, mask,
+                                          out_dtype=B.AERIS_DT_F32)
+    torch.cuda.synchronize()
+    phi = ro.angles(H, W, d, win, shift, base, ro.POS_GRID)
+
+    def turn(x_hwd, inverse=False):
+        return ro.rotate(x_hwd[None, :, :, None, :], phi, inverse=inverse)[0, :, :, 0, :]
+
+    for (wy, wx, h) in [(0, 4, 0), (1, 23, 17)]:           # interior window, corner window
+        sl = lambda t: to_f64(t[0, :, :, h, :])
+        qr, kr = round_bf16(turn(sl(tq))), round_bf16(turn(sl(tk)))
+        res = orc.winattn_pair(qr, kr, sl(tv), sl(tdo), H, W, win, shift, mask, None, wy, wx)
+        y, x = res["y"], res["x"]
+        check("o", sl(o)[y, x], res["o"], False)
+        assert np.abs(to_f64(lse[0, h])[y, x] - res["lse"]).max() <= LSE_ABS
+        check("dv", sl(dv)[y, x], res["dv"], False)
+        for name, got, ref_rot in (("dq", dq, res["dq"]), ("dk", dk, res["dk"])):
+            full = np.zeros((H, W, d))
+            full[y, x] = ref_rot
+            check(name, sl(got)[y, x], turn(full, inverse=True)[y, x], False)
