@@ -117,3 +117,27 @@ def test_window_list_arguments_rejected_before_launch():
     # four of 128 windows need 1/32 of the full workspace (plus padding): 16 bytes are too few
     assert lib.aeris_winattn_bwd_windows(ctypes.byref(p), a, 4, a, a, a, a, a, a, a, a, a, a,
                                          16, None) == -8
+
+
+def test_header_is_plain_c_and_callable_from_c(tmp_path):
+    """Compiles tests/c/abi_check.c as C99 against include/aeris_winattn.h, links it to the
+    library and runs it: struct layout as the binding assumes, host-only calls work from C."""
+    import subprocess
+    B.load()
+    exe = str(tmp_path / "abi_check")
+    lib_dir = os.path.dirname(B.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "c", "abi_check.c"), "-o", exe,
+                    "-L", lib_dir, "-laeris_winattn", "-Wl,-rpath," + lib_dir,
+                    "-Wl,-rpath,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"], check=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout
+    got = dict(l.split(" ", 1) for l in out.strip().splitlines())
+    assert int(got["sizeof_params"]) == ctypes.sizeof(B.aeris_winattn_params)
+    assert int(got["offset_strides"]) == B.aeris_winattn_params.qkv_tok_stride.offset
+    assert int(got["sizeof_rope"]) == ctypes.sizeof(B.aeris_rope_params)
+    assert int(got["version"]) == B.aeris_winattn_version()
+    assert got["validate"] == "0"
+    assert got["validate_bad"].startswith("-3 window does not divide")
+    assert int(got["bwd_ws"]) == 2 * (1 * 128 * 4 * 64 + 64) * 4
+    assert int(got["rope_fwd_ws"]) == 64 * 128 * 4 * 32 * 2
+    assert got["null_fwd"] == "-1" and got["null_rope"] == "-1"

@@ -177,6 +177,14 @@ def test_paper_window_60x60(d):
              outs=(B.AERIS_DT_BF16,))
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_maximum_window_tokens(d):
+    # one 64 x 128 window = 8192 tokens, the largest the on-chip token table holds; shifted, so the
+    # window splits into four mask regions of 2048 tokens
+    run_case((1, 64, 128, 1, d), (64, 128), (32, 64), B.AERIS_MASK_SWIN, kind="blend", seed=95,
+             outs=(B.AERIS_DT_BF16,))
+
+
 def test_packed_qkv_strides():
     shape, win, shift, mask = (1, 24, 24, 2, 64), (12, 12), (6, 6), B.AERIS_MASK_SWIN
     Bn, H, W, nh, d = shape
