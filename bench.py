@@ -109,7 +109,7 @@ def main():
 
     U = {s: Bn * nh * unmasked_pairs(H, W, win, s, mask) for s in wl["layers"]}
     model_flops = sum((12 if wl["bwd"] else 4) * d * U[s] for s in wl["layers"])
-    kernel_flops = {"fwd": 4, "dq": 6, "dkdv": 8, "delta": 0}
+    kernel_flops = {"fwd": 4, "dq": 6, "dkdv": 8}
     events = {k: [] for k in kernel_flops}
 
     def timed(name, fn, record):
@@ -128,8 +128,10 @@ def main():
             timed("fwd", lambda: B.aeris_winattn_fwd(tq, tk, tv, win, s, mask, o=o, lse=lse),
                   record)
             if wl["bwd"]:
-                for name, st in (("delta", B.AERIS_BWD_DELTA), ("dkdv", B.AERIS_BWD_DKDV),
-                                 ("dq", B.AERIS_BWD_DQ)):
+                # the backward pass as aeris_winattn_bwd runs it, one event pair per kernel: the
+                # dQ kernel (which also produces delta and LSE*log2e), then the dK/dV kernel
+                for name, st in (("dq", B.AERIS_BWD_DELTA | B.AERIS_BWD_DQ),
+                                 ("dkdv", B.AERIS_BWD_DKDV)):
                     timed(name, lambda: B.aeris_winattn_bwd_stages(
                         tq, tk, tv, o, lse, tdo, win, s, mask, dq=dq, dk=dk, dv=dv,
                         workspace=ws, stages=st), record)

@@ -122,11 +122,13 @@ int aeris_winattn_bwd(const aeris_winattn_params* p, const void* q, const void* 
                       void* dq, void* dk, void* dv, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
 
-/* The backward pass is three kernels; this variant runs a subset, in the order
+/* The backward pass has three stages; this variant runs a subset, in the order
  * delta, dq, dkdv (for profiling one kernel, or to put dq and dkdv on different
  * streams).  AERIS_BWD_DQ and AERIS_BWD_DKDV read what AERIS_BWD_DELTA left in
- * `workspace`, so that stage must have completed on it first.  Outputs of
- * stages that are not selected are left untouched.  stages == AERIS_BWD_ALL is
+ * `workspace`, so that stage must have completed on it first.  When DELTA and DQ
+ * are selected together the dQ kernel produces the statistics itself (the same
+ * bits) and no separate pass over o and d_o is launched.  Outputs of stages that
+ * are not selected are left untouched.  stages == AERIS_BWD_ALL is
  * aeris_winattn_bwd. */
 enum { AERIS_BWD_DELTA = 1, AERIS_BWD_DQ = 2, AERIS_BWD_DKDV = 4, AERIS_BWD_ALL = 7 };
 int aeris_winattn_bwd_stages(const aeris_winattn_params* p, const void* q, const void* k,

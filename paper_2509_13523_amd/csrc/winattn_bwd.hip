@@ -104,8 +104,12 @@ constexpr size_t dq_smem_bytes(int T) {
 template <int D, typename OutT>
 __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
     KParams p, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-    const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
-    const float* __restrict__ delta, const float* __restrict__ lse2v, OutT* __restrict__ dq) {
+    const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o, const OutT* __restrict__ o,
+    const float* __restrict__ lse, float* __restrict__ delta, float* __restrict__ lse2v,
+    OutT* __restrict__ dq, int make_stats) {
+  // make_stats != 0: this kernel computes delta and LSE*log2e of its resident queries itself
+  // (bit for bit what winattn_delta_kernel computes) and leaves them in the workspace for the
+  // dK/dV kernel, so the separate pass over O and dO is not needed; otherwise it reads them.
   using Tl = Tile<D>;
   constexpr uint32_t kBuf = 2 * Tl::kBytes;   // one buffer: K tile, V tile
   extern __shared__ __align__(16) unsigned char smem[];
@@ -116,8 +120,21 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
   int pair, qt;
   if (!block_to_work(p, pair, qt)) return;
 
+  if (make_stats && blockIdx.x == 0 && threadIdx.x < kStream) {
+    // padding behind the last pair: streamed tiles read up to 63 entries past a window's end
+    delta[(long long)p.n_pairs * p.T + threadIdx.x] = 0.f;
+    lse2v[(long long)p.n_pairs * p.T + threadIdx.x] = 0.f;
+  }
   Window win;
-  if (!win.init(p, pair)) return;
+  if (!win.init(p, pair)) {
+    // a skipped window still gets finite statistics (see winattn_delta_kernel)
+    const int t = qt * kResident + (int)threadIdx.x;
+    if (make_stats && threadIdx.x < kResident && t < p.T) {
+      delta[(long long)pair * p.T + t] = 0.f;
+      lse2v[(long long)pair * p.T + t] = 0.f;
+    }
+    return;
+  }
   build_token_table(p, win, tok_grid);
   __syncthreads();
 
@@ -157,8 +174,38 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_dq_kernel(
       doreg[kk] = *reinterpret_cast<const bf16x8*>(dorow + kk * 16);
     }
   }
-  float lse2 = lse2v[(long long)pair * p.T + rg.tok];
-  float delta_q = delta[(long long)pair * p.T + rg.tok];
+  float lse2, delta_q;
+  if (make_stats) {
+    // delta = sum_c dO*O with the summation tree of winattn_delta_kernel: an fma chain over
+    // the 8 channels of a chunk, then pairwise over the chunk index (bit 0 first).  This lane
+    // holds chunks 2*kk + g; the partner lane (l ^ 32) holds the other chunk of every pair.
+    const OutT* orow = o + o_base + (long long)q_grid * p.o_tok + 8 * g;
+    float part[D / 16];
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      float a[8];
+      load8(orow + kk * 16, a);
+      float acc1 = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc1 = __builtin_fmaf(a[i], (float)doreg[kk][i], acc1);
+      const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc1), __float_as_uint(acc1),
+                                                       false, false);
+      part[kk] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);   // chunk 2kk + chunk 2kk+1
+    }
+#pragma unroll
+    for (int s2 = 1; s2 < D / 16; s2 <<= 1)
+#pragma unroll
+      for (int kk = 0; kk < D / 16; kk += 2 * s2) part[kk] += part[kk + s2];
+    delta_q = part[0];
+    lse2 = lse[((long long)win.b * p.nh + win.head) * plane + q_grid] * kLog2e;
+    if (rg.valid && g == 0) {
+      delta[(long long)pair * p.T + rg.tok] = delta_q;
+      lse2v[(long long)pair * p.T + rg.tok] = lse2;
+    }
+  } else {
+    lse2 = lse2v[(long long)pair * p.T + rg.tok];
+    delta_q = delta[(long long)pair * p.T + rg.tok];
+  }
   typename Tl::Lanes la;
   la.init(tiles, lane);
 #pragma unroll
@@ -552,7 +599,9 @@ static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const v
 
   float* delta = workspace;
   float* lse2 = workspace + stat_entries(kp);
-  if (stages & 1u) {
+  // with both stages requested the dQ kernel produces the statistics itself
+  const bool fused_stats = (stages & 3u) == 3u;
+  if ((stages & 1u) && !fused_stats) {
     constexpr int kTokens = kThreads / (D / 8);
     const long long dblocks = (long long)kp.n_pairs * ((kp.T + kTokens - 1) / kTokens);
     hipLaunchKernelGGL((winattn_delta_kernel<D, OutT>), dim3((unsigned)dblocks), dim3(kThreads),
@@ -566,8 +615,8 @@ static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const v
     auto kern = winattn_dq_kernel<D, OutT>;
     if (!allow_smem(kern, smem)) return -1;
     hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, qp, kp_, vp, dop,
-                       static_cast<const float*>(delta), static_cast<const float*>(lse2),
-                       static_cast<OutT*>(dq));
+                       static_cast<const OutT*>(o), lse, delta, lse2, static_cast<OutT*>(dq),
+                       fused_stats ? 1 : 0);
     if (hipGetLastError() != hipSuccess) return -1;
   }
   if constexpr (D == 128) {   // software-pipelined kernel; the generic one is not built for it
