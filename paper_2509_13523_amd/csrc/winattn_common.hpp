@@ -92,6 +92,7 @@ struct Window {
   int b, head, wy, wx;
   int split_r, split_c;   // first row / column of the second region (== side if no seam)
   int wc0, wc1;           // columns in the left / right region
+  float inv_wc0, inv_wc1; // their reciprocals (for the row/column split in grid_index)
   int s01, s10, s11, T;   // enumeration start of regions (0,1), (1,0), (1,1)
 
   // False (uniformly for the workgroup) if a listed window index is out of range: the
@@ -111,6 +112,8 @@ struct Window {
     split_c = lon_seam ? p.ws_w - p.s_w : p.ws_w;
     wc0 = split_c;
     wc1 = p.ws_w - split_c;
+    inv_wc0 = 1.0f / (float)wc0;
+    inv_wc1 = 1.0f / (float)(wc1 > 0 ? wc1 : 1);
     const int hr0 = split_r, hr1 = p.ws_h - split_r;
     s01 = hr0 * wc0;
     s10 = s01 + hr0 * wc1;
@@ -128,13 +131,18 @@ struct Window {
   // Grid point (row-major index y*W + x) of token t: partition + cyclic shift.
   __device__ __forceinline__ int grid_index(const KParams& p, int t) const {
     int lo, w, r0, c0;
-    if (t < s01) { lo = 0; w = wc0; r0 = 0; c0 = 0; }
-    else if (t < s10) { lo = s01; w = wc1; r0 = 0; c0 = split_c; }
-    else if (t < s11) { lo = s10; w = wc0; r0 = split_r; c0 = 0; }
-    else { lo = s11; w = wc1; r0 = split_r; c0 = split_c; }
+    float inv;
+    if (t < s01) { lo = 0; w = wc0; inv = inv_wc0; r0 = 0; c0 = 0; }
+    else if (t < s10) { lo = s01; w = wc1; inv = inv_wc1; r0 = 0; c0 = split_c; }
+    else if (t < s11) { lo = s10; w = wc0; inv = inv_wc0; r0 = split_r; c0 = 0; }
+    else { lo = s11; w = wc1; inv = inv_wc1; r0 = split_r; c0 = split_c; }
+    // u / w without an integer division: u < 8192, so the float quotient is off by at most
+    // one, which the remainder test repairs (a workgroup evaluates this T/256 times per thread)
     const int u = t - lo;
-    const int rr = u / w;
-    const int cc = u - rr * w;
+    int rr = (int)((float)u * inv);
+    int cc = u - rr * w;
+    if (cc < 0) { rr -= 1; cc += w; }
+    else if (cc >= w) { rr += 1; cc -= w; }
     int y = wy * p.ws_h + r0 + rr + p.s_h;
     int x = wx * p.ws_w + c0 + cc + p.s_w;
     if (y >= p.H) y -= p.H;
