@@ -306,3 +306,39 @@ def test_config5_ensemble_member_fwd_bwd_sampled():
     samples = [(0, 5, 5, 1), (0, 11, 23, 6), (1, 11, 2, 9), (1, 7, 23, 15)]
     sampled_check((2, 720, 1440, 16, 128), (60, 60), (30, 30), B.AERIS_MASK_SWIN, "blend", 5001,
                   True, samples, sigmas=[0.1, 2.0])
+
+
+def test_forward_backward_replay_from_a_hip_graph():
+    """The library only launches kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so a forward+backward pair can be captured once and replayed.  Every replay
+    must reproduce the eager result bit for bit, with other eager work in between."""
+    shape, win, shift, mask = (1, 60, 120, 2, 128), (30, 30), (15, 15), B.AERIS_MASK_SWIN
+    Bn, H, W, nh, d = shape
+    bits = synth.make_inputs("normal", 97, shape, 4)
+    tq, tk, tv, tdo = [to_dev(b) for b in bits]
+    o = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((Bn, nh, H, W), dtype=torch.float32, device="cuda")
+    grads = [torch.empty_like(o) for _ in range(3)]
+    p = B.make_params(shape, win, shift, mask)
+    ws = torch.empty(B.aeris_winattn_bwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+
+    def run():
+        B.aeris_winattn_fwd(tq, tk, tv, win, shift, mask, o=o, lse=lse)
+        B.aeris_winattn_bwd_stages(tq, tk, tv, o, lse, tdo, win, shift, mask, dq=grads[0],
+                                   dk=grads[1], dv=grads[2], workspace=ws)
+
+    run()                                   # eager reference (also sets the kernels' LDS limits)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (o, lse, *grads)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for rep in range(3):
+        for t in (o, lse, *grads):
+            t.fill_(float("nan"))           # eager work between the replays
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((o, lse, *grads), want):
+            assert torch.equal(got, ref), rep
