@@ -342,3 +342,23 @@ def test_forward_backward_replay_from_a_hip_graph():
         torch.cuda.synchronize()
         for got, ref in zip((o, lse, *grads), want):
             assert torch.equal(got, ref), rep
+
+
+def test_seeded_sweep_of_small_shapes():
+    """Forty seeded random small problems: window sides from 1 to 24 (ragged tiles, single-token
+    windows, non-square windows), any shift including one-axis shifts, every mask policy, every
+    head_dim, batch and head counts 1 to 3, default and overridden scale, both output types."""
+    rng = np.random.default_rng(20240607)
+    for case in range(40):
+        wh, ww = int(rng.integers(1, 25)), int(rng.integers(1, 25))
+        nwy, nwx = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        sh = int(rng.integers(0, wh)) if rng.random() < 0.8 else 0
+        sw = int(rng.integers(0, ww)) if rng.random() < 0.8 else 0
+        d = int(rng.choice([32, 64, 128]))
+        shape = (int(rng.integers(1, 3)), wh * nwy, ww * nwx, int(rng.integers(1, 4)), d)
+        mask = int(rng.choice(POLICIES))
+        scale = None if rng.random() < 0.7 else float(rng.uniform(0.05, 0.15))
+        out = B.AERIS_DT_F32 if rng.random() < 0.5 else B.AERIS_DT_BF16
+        print("case", case, shape, (wh, ww), (sh, sw), mask, scale, out, flush=True)
+        run_case(shape, (wh, ww), (sh, sw), mask, kind="normal", seed=7000 + case, scale=scale,
+                 outs=(out,))

@@ -158,3 +158,22 @@ def test_rope_band_share_full_size_sampled():
             full = np.zeros((H, W, d))
             full[y, x] = ref_rot
             check(name, sl(got)[y, x], turn(full, inverse=True)[y, x], False)
+
+
+def test_rope_seeded_sweep_of_small_shapes():
+    """Twelve seeded random small problems with the rotary embedding: any window shape and shift,
+    both position modes, bases from 10 to 10000, every mask policy and head_dim."""
+    rng = np.random.default_rng(20240608)
+    for case in range(12):
+        wh, ww = int(rng.integers(2, 21)), int(rng.integers(2, 21))
+        nwy, nwx = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        sh, sw = int(rng.integers(0, wh)), int(rng.integers(0, ww))
+        d = int(rng.choice([32, 64, 128]))
+        shape = (int(rng.integers(1, 3)), wh * nwy, ww * nwx, int(rng.integers(1, 3)), d)
+        mask = int(rng.choice([B.AERIS_MASK_NONE, B.AERIS_MASK_LAT, B.AERIS_MASK_SWIN]))
+        mode = int(rng.choice(MODES))
+        base = float(rng.choice([10.0, 100.0, 10000.0]))
+        out = B.AERIS_DT_F32 if rng.random() < 0.5 else B.AERIS_DT_BF16
+        print("case", case, shape, (wh, ww), (sh, sw), mask, mode, base, out, flush=True)
+        run_rope_case(shape, (wh, ww), (sh, sw), mask, mode, base=base, seed=7100 + case,
+                      outs=(out,))
