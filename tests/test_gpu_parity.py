@@ -362,3 +362,22 @@ def test_seeded_sweep_of_small_shapes():
         print("case", case, shape, (wh, ww), (sh, sw), mask, scale, out, flush=True)
         run_case(shape, (wh, ww), (sh, sw), mask, kind="normal", seed=7000 + case, scale=scale,
                  outs=(out,))
+
+
+@pytest.mark.parametrize("d", [32, 128])
+def test_very_peaked_rows_exercise_the_running_maximum(d):
+    """Scale 16x the default: logits have a standard deviation of 16 and single keys dominate
+    their rows, so the lagging running maximum is raised (and the accumulators rescaled) many
+    times per row, and most probabilities underflow.  Forward outputs and LSE keep the plain
+    tolerance; the LSE bound gets a relative part (|LSE| approaches 100)."""
+    shape, win, shift, mask = (1, 32, 64, 2, d), (16, 32), (8, 16), B.AERIS_MASK_SWIN
+    scale = 16.0 / np.sqrt(d)
+    bits = synth.make_inputs("normal", 99, shape, 3)
+    q64, k64, v64 = [synth.bf16_bits_to_f64(b) for b in bits]
+    tq, tk, tv = [to_dev(b) for b in bits]
+    o_ref, lse_ref = orc.winattn_fwd(q64, k64, v64, win, shift, mask, scale)
+    assert np.abs(lse_ref).max() > 50.0
+    o, lse = B.aeris_winattn_fwd(tq, tk, tv, win, shift, mask, scale, out_dtype=B.AERIS_DT_F32)
+    torch.cuda.synchronize()
+    check("o", o, o_ref, False)
+    assert (np.abs(to_f64(lse) - lse_ref) <= LSE_ABS + 1e-5 * np.abs(lse_ref)).all()
