@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-pairs", type=int, default=64)
+    ap.add_argument("--no-mfma-loop", action="store_true",
+                    help="skip the register-operand MFMA loop that measures the MFMA rate this "
+                         "machine sustains under its power limit (about one second)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="end with three 1 GiB read + 1 GiB write elementwise kernels "
                          "(the last three dispatches), to scale rocprofv3 FETCH_SIZE/WRITE_SIZE")
@@ -180,6 +183,23 @@ def main():
     tensor = 2.0 * Bn * H * W * nh * d
     step_bytes = len(wl["layers"]) * ((4 + (13 if wl["bwd"] else 0)) * tensor)
     out["algorithmic_gbs"] = round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1)
+
+    if not args.no_mfma_loop:
+        # the MFMA rate the machine sustains on random operands (power-limited clock), measured
+        # right after the timed steps: context for roofline.frac, which stays against the
+        # published peak
+        sink = torch.empty(512 * 256, dtype=torch.float32, device=dev)
+        B.aeris_mfma_loop_probe(512, 20000, True, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flop = B.aeris_mfma_loop_probe(512, 600000, True, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        loop_tflops = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        out["roofline"]["measured_mfma_loop_tflops"] = round(loop_tflops, 1)
+        out["roofline"]["frac_of_measured_loop"] = round(achieved / loop_tflops, 4)
+        del sink
 
     if args.calibrate_copy:
         a = torch.zeros(1 << 28, dtype=torch.float32, device=dev)

@@ -19,7 +19,7 @@ EXPORTS = ("aeris_winattn_fwd", "aeris_winattn_bwd", "aeris_winattn_bwd_stages",
            "aeris_winattn_bwd_workspace_bytes",
            "aeris_winattn_validate", "aeris_winattn_strerror", "aeris_winattn_version",
            "aeris_winattn_fwd_windows", "aeris_winattn_bwd_windows",
-           "aeris_rope2d_apply", "aeris_winattn_rope_fwd_workspace_bytes",
+           "aeris_mfma_loop_probe", "aeris_rope2d_apply", "aeris_winattn_rope_fwd_workspace_bytes",
            "aeris_winattn_rope_bwd_workspace_bytes", "aeris_winattn_rope_fwd",
            "aeris_winattn_rope_bwd")
 
@@ -81,6 +81,8 @@ def load():
     lib.aeris_winattn_bwd_windows.argtypes = [P, vp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp, vp,
                                               vp, vp, ctypes.c_size_t, vp]
     lib.aeris_winattn_bwd_windows.restype = ctypes.c_int
+    lib.aeris_mfma_loop_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
+    lib.aeris_mfma_loop_probe.restype = ctypes.c_int
     R = ctypes.POINTER(aeris_rope_params)
     lib.aeris_rope2d_apply.argtypes = [P, R, vp, vp, ctypes.c_int32, vp]
     lib.aeris_rope2d_apply.restype = ctypes.c_int
@@ -297,3 +299,14 @@ def aeris_winattn_bwd_windows(q, k, v, o, lse, d_o, win, shift, windows, dq, dk,
     if rc != 0:
         raise AerisError(rc, "aeris_winattn_bwd_windows")
     return dq, dk, dv
+
+
+def aeris_mfma_loop_probe(blocks, iters, random_operands, sink):
+    """Measurement aid: register-operand MFMA loop; sink is a float32 device tensor of blocks*256."""
+    import torch
+    assert sink.is_cuda and sink.dtype == torch.float32 and sink.numel() >= blocks * 256
+    rc = load().aeris_mfma_loop_probe(int(blocks), int(iters), 1 if random_operands else 0,
+                                      sink.data_ptr(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_mfma_loop_probe")
+    return blocks * 4 * iters * 8 * 32768.0

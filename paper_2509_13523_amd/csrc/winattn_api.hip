@@ -302,6 +302,17 @@ int aeris_winattn_rope_bwd(const aeris_winattn_params* p, const aeris_rope_param
   return AERIS_OK;
 }
 
+int aeris_mfma_loop_probe(int32_t blocks, int32_t iters, int32_t random_operands, float* sink,
+                          void* hip_stream) {
+  if (!sink) return AERIS_ERR_NULL_POINTER;
+  if (blocks < 1 || blocks > 65536 || iters < 1) return AERIS_ERR_INVALID_SHAPE;
+  if (misaligned(sink)) return AERIS_ERR_MISALIGNED;
+  if (aeris::launch_mfma_loop(blocks, iters, random_operands != 0, sink,
+                              static_cast<hipStream_t>(hip_stream)) != 0)
+    return AERIS_ERR_HIP_LAUNCH;
+  return AERIS_OK;
+}
+
 const char* aeris_winattn_strerror(int code) {
   switch (code) {
     case AERIS_OK: return "ok";

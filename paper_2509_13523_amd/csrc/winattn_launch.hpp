@@ -24,6 +24,10 @@ int launch_dkdv_pipe128(const KParams& kp, bool out_f32, const void* q, const vo
 int launch_rope(const KParams& kp, int head_dim, const void* x, long long x_tok, long long x_head,
                 void* y, long long y_tok, long long y_head, bool inverse, hipStream_t stream);
 
+// Measurement aid: `blocks` workgroups each issue 8 * iters MFMAs (32x32x16 bf16) per wave on
+// register operands and write one float per thread to sink[blocks * 256].
+int launch_mfma_loop(int blocks, int iters, bool random_operands, float* sink, hipStream_t stream);
+
 // Bytes of device workspace launch_bwd needs for these parameters.
 size_t bwd_workspace_bytes(const KParams& kp);
 
