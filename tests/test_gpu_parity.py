@@ -302,10 +302,11 @@ def test_config4_band_share_fwd_bwd_sampled():
 
 
 def test_config5_ensemble_member_fwd_bwd_sampled():
-    # the bench workload's launch shape, two ensemble members (noise levels 0.1 and 2.0)
-    samples = [(0, 5, 5, 1), (0, 11, 23, 6), (1, 11, 2, 9), (1, 7, 23, 15)]
-    sampled_check((2, 720, 1440, 16, 128), (60, 60), (30, 30), B.AERIS_MASK_SWIN, "blend", 5001,
-                  True, samples, sigmas=[0.1, 2.0])
+    # exactly the bench workload's launch (B = 4, noise levels 0.1, 0.5, 1.0, 2.0); samples from the
+    # smoothest and the noisiest member: interior, corner, lat-seam and lon-seam windows
+    samples = [(0, 5, 5, 1), (0, 11, 23, 6), (3, 11, 2, 9), (3, 7, 23, 15)]
+    sampled_check((4, 720, 1440, 16, 128), (60, 60), (30, 30), B.AERIS_MASK_SWIN, "blend", 5001,
+                  True, samples, sigmas=[0.1, 0.5, 1.0, 2.0])
 
 
 def test_forward_backward_replay_from_a_hip_graph():
