@@ -177,6 +177,13 @@ def test_paper_window_60x60(d):
              outs=(B.AERIS_DT_BF16,))
 
 
+def test_config5_unshifted_layer_fwd_bwd_sampled():
+    # the other layer of the bench step: shift 0 (no seam, no mask effect)
+    samples = [(1, 0, 0, 3), (2, 6, 17, 12)]
+    sampled_check((4, 720, 1440, 16, 128), (60, 60), (0, 0), B.AERIS_MASK_SWIN, "blend", 5001,
+                  True, samples, sigmas=[0.1, 0.5, 1.0, 2.0])
+
+
 @pytest.mark.parametrize("d", [64, 128])
 def test_maximum_window_tokens(d):
     # one 64 x 128 window = 8192 tokens, the largest the on-chip token table holds; shifted, so the
