@@ -581,13 +581,6 @@ __global__ __launch_bounds__(kThreads, D == 128 ? 1 : 2) void winattn_dkdv_kerne
     }
 }
 
-template <typename K>
-static bool allow_smem(K kern, size_t smem) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)smem) == hipSuccess;
-}
-
 template <int D, typename OutT>
 static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const void* v,
                         const void* o, const float* lse, const void* d_o, void* dq, void* dk,
@@ -613,7 +606,7 @@ static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const v
   if (stages & 2u) {
     const size_t smem = dq_smem_bytes<D>(kp.T);
     auto kern = winattn_dq_kernel<D, OutT>;
-    if (!allow_smem(kern, smem)) return -1;
+    if (!allow_full_lds<winattn_dq_kernel<D, OutT>>()) return -1;
     hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, qp, kp_, vp, dop,
                        static_cast<const OutT*>(o), lse, delta, lse2, static_cast<OutT*>(dq),
                        fused_stats ? 1 : 0);
@@ -626,7 +619,7 @@ static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const v
   } else if (stages & 4u) {
     const size_t smem = dkdv_smem_bytes<D>(kp.T);
     auto kern = winattn_dkdv_kernel<D, OutT>;
-    if (!allow_smem(kern, smem)) return -1;
+    if (!allow_full_lds<winattn_dkdv_kernel<D, OutT>>()) return -1;
     hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, qp, kp_, vp, dop,
                        static_cast<const float*>(delta), static_cast<const float*>(lse2),
                        static_cast<OutT*>(dk), static_cast<OutT*>(dv));

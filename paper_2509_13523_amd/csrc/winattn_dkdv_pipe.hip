@@ -341,9 +341,7 @@ static int launch_t(const KParams& kp, const void* q, const void* k, const void*
                     hipStream_t stream) {
   const size_t smem = dkdv_pipe_smem_bytes<D>(kp.T);
   auto kern = winattn_dkdv_pipe_kernel<D, OutT>;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-    return -1;
+  if (!allow_full_lds<winattn_dkdv_pipe_kernel<D, OutT>>()) return -1;
   hipLaunchKernelGGL(kern, dim3(grid_blocks(kp)), dim3(kThreads), smem, stream, kp,
                      static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
                      static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(d_o), delta, lse2,

@@ -286,9 +286,7 @@ static int launch_fwd_t(const KParams& kp, const void* q, const void* k, const v
   const int n_blocks = grid_blocks(kp);
   const size_t smem = fwd_smem_bytes<D>(kp.T);
   auto kern = winattn_fwd_kernel<D, OutT>;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-    return -1;
+  if (!allow_full_lds<winattn_fwd_kernel<D, OutT>>()) return -1;
   hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp,
                      static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
                      static_cast<const bf16_t*>(v), static_cast<OutT*>(o), lse);

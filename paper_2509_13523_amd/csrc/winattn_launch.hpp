@@ -2,9 +2,29 @@
 // the launches were enqueued and -1 when HIP reported a launch error.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <atomic>
+
 #include "winattn_common.hpp"
 
 namespace aeris {
+
+// Lets kernel `Kern` use the whole LDS of a CU (160 KB on gfx950) as dynamic shared memory.
+// The attribute is set once per kernel and device and remembered, which keeps it off the
+// launch path of small problems; what a launch actually requests still decides occupancy.
+template <auto Kern>
+inline bool allow_full_lds() {
+  static std::atomic<unsigned> configured{0};   // one bit per device ordinal (mod 32)
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  const unsigned bit = 1u << (dev & 31);
+  if (configured.load(std::memory_order_acquire) & bit) return true;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(Kern),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+    return false;
+  configured.fetch_or(bit, std::memory_order_release);
+  return true;
+}
 
 int launch_fwd(const KParams& kp, int head_dim, bool out_f32, const void* q, const void* k,
                const void* v, void* o, float* lse, hipStream_t stream);
