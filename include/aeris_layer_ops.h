@@ -1,0 +1,104 @@
+/*
+ * aeris_layer_ops.h -- C ABI of the element-wise operations around the window attention in an
+ * AERIS transformer layer (MI355X / gfx950), in the same library as aeris_winattn.h.
+ *
+ * The AERIS paper ("AERIS Model Architecture") builds every layer from a pre-RMSNorm (in place
+ * of LayerNorm), an attention or SwiGLU branch, and adaptive-layer-norm values alpha, beta,
+ * gamma that a layer-specific linear map derives from the diffusion-time embedding.  It prints
+ * no formulas; the ones below are those of the works it cites for each part.  The matrix
+ * products of a layer (QKV, output and SwiGLU projections) are plain GEMMs and are NOT part of
+ * this library.
+ *
+ * Rows are tokens.  Activations are bf16, row-major [n_rows, channels], rows contiguous
+ * (stride = channels).  The sample of row i is i / rows_per_sample: the tokens of one sample
+ * share one diffusion time and therefore one (alpha, beta, gamma).  Parameters and conditioning
+ * vectors are fp32: w [channels]; alpha, beta, gamma [n_samples, channels] with
+ * n_samples = n_rows / rows_per_sample.  All arithmetic is fp32; bf16 results are rounded to
+ * nearest even.  Sums over tokens are taken in a fixed order (no atomics): results are bitwise
+ * reproducible from call to call.
+ *
+ * Limits: channels % 8 == 0 and 8 <= channels <= AERIS_MAX_CHANNELS; hidden % 8 == 0;
+ * n_rows % rows_per_sample == 0.  Pointers are DEVICE pointers, 16-byte aligned, owned by the
+ * caller; inputs are read-only and outputs fully overwritten.  The library allocates nothing and
+ * never synchronises: calls only enqueue kernels on `hip_stream` (a hipStream_t passed as
+ * void*; NULL is the default stream).  Errors are the AERIS_ERR_* codes of aeris_winattn.h;
+ * arguments are checked before anything is launched.
+ */
+#ifndef AERIS_LAYER_OPS_H
+#define AERIS_LAYER_OPS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AERIS_MAX_CHANNELS 4096
+
+/*
+ * Pre-RMSNorm with adaptive modulation (Model Architecture: pre RMSNorm; alpha, beta, gamma of
+ * the adaptive layer norm).  For every row:
+ *     r = (mean_c x_c^2 + eps)^(-1/2),  h_c = x_c r w_c (1 + gamma_{b,c}) + beta_{b,c}.
+ * Outputs h [n_rows, channels] bf16 and r [n_rows] fp32 (kept for the backward pass; r may be
+ * NULL if it is not wanted).
+ */
+int aeris_rmsnorm_adaln_fwd(const void* x, const float* w, const float* gamma, const float* beta,
+                            float eps, int64_t n_rows, int64_t rows_per_sample, int32_t channels,
+                            void* h, float* r, void* hip_stream);
+
+/*
+ * Backward of the above, given dh [n_rows, channels] bf16 and the r of the forward call:
+ *     n = x r,  dn = dh w (1 + gamma),  dx = r (dn - n mean_c(dn n))           bf16
+ *     dbeta_{b,c}  = sum_{rows of b} dh_c
+ *     dgamma_{b,c} = w_c sum_{rows of b} dh_c n_c
+ *     dw_c         = sum_b (1 + gamma_{b,c}) sum_{rows of b} dh_c n_c          fp32
+ * dw, dgamma, dbeta may each be NULL (not wanted).  `workspace` holds the per-workgroup partial
+ * column sums; its size comes from the function below.
+ */
+size_t aeris_rmsnorm_adaln_bwd_workspace_bytes(int64_t n_rows, int64_t rows_per_sample,
+                                               int32_t channels);
+int aeris_rmsnorm_adaln_bwd(const void* x, const float* w, const float* gamma, const float* r,
+                            const void* dh, int64_t n_rows, int64_t rows_per_sample,
+                            int32_t channels, void* dx, float* dw, float* dgamma, float* dbeta,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Gated residual connection (Model Architecture: alpha of the adaptive layer norm gates the
+ * branch before it joins the residual stream):  out = x + alpha_b * y, all bf16.
+ * `out` may alias x or y.
+ */
+int aeris_gate_residual_fwd(const void* x, const void* y, const float* alpha, int64_t n_rows,
+                            int64_t rows_per_sample, int32_t channels, void* out,
+                            void* hip_stream);
+
+/*
+ * Backward of the gated residual, given dout (the gradient with respect to x is dout itself):
+ *     dy = alpha_b * dout   (bf16),   dalpha_{b,c} = sum_{rows of b} dout_c y_c   (fp32).
+ * dy may alias dout.  dalpha may be NULL.
+ */
+size_t aeris_gate_residual_bwd_workspace_bytes(int64_t n_rows, int64_t rows_per_sample,
+                                               int32_t channels);
+int aeris_gate_residual_bwd(const void* y, const float* alpha, const void* dout, int64_t n_rows,
+                            int64_t rows_per_sample, int32_t channels, void* dy, float* dalpha,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * SwiGLU gate (Model Architecture: SwiGLU in the fully connected layers) on the packed up
+ * projection uv [n_rows, 2*hidden] = [u | v]:  g = silu(u) * v,  silu(u) = u / (1 + exp(-u)).
+ * g is [n_rows, hidden] bf16.
+ */
+int aeris_swiglu_fwd(const void* uv, int64_t n_rows, int32_t hidden, void* g, void* hip_stream);
+
+/*
+ * Backward of the gate, given dg [n_rows, hidden]:  with s = 1 / (1 + exp(-u)),
+ *     du = dg v s (1 + u (1 - s)),   dv = dg u s;   duv [n_rows, 2*hidden] = [du | dv] bf16.
+ * duv may alias uv.
+ */
+int aeris_swiglu_bwd(const void* uv, const void* dg, int64_t n_rows, int32_t hidden, void* duv,
+                     void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AERIS_LAYER_OPS_H */

@@ -21,7 +21,12 @@ EXPORTS = ("aeris_winattn_fwd", "aeris_winattn_bwd", "aeris_winattn_bwd_stages",
            "aeris_winattn_fwd_windows", "aeris_winattn_bwd_windows",
            "aeris_mfma_loop_probe", "aeris_rope2d_apply", "aeris_winattn_rope_fwd_workspace_bytes",
            "aeris_winattn_rope_bwd_workspace_bytes", "aeris_winattn_rope_fwd",
-           "aeris_winattn_rope_bwd")
+           "aeris_winattn_rope_bwd",
+           # include/aeris_layer_ops.h
+           "aeris_rmsnorm_adaln_fwd", "aeris_rmsnorm_adaln_bwd_workspace_bytes",
+           "aeris_rmsnorm_adaln_bwd", "aeris_gate_residual_fwd",
+           "aeris_gate_residual_bwd_workspace_bytes", "aeris_gate_residual_bwd",
+           "aeris_swiglu_fwd", "aeris_swiglu_bwd")
 
 
 class aeris_winattn_params(ctypes.Structure):
@@ -95,6 +100,24 @@ def load():
     lib.aeris_winattn_rope_bwd.argtypes = [P, R, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                            ctypes.c_size_t, vp]
     lib.aeris_winattn_rope_bwd.restype = ctypes.c_int
+    i64, i32, f32, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+    lib.aeris_rmsnorm_adaln_fwd.argtypes = [vp, vp, vp, vp, f32, i64, i64, i32, vp, vp, vp]
+    lib.aeris_rmsnorm_adaln_fwd.restype = ctypes.c_int
+    lib.aeris_rmsnorm_adaln_bwd_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.aeris_rmsnorm_adaln_bwd_workspace_bytes.restype = sz
+    lib.aeris_rmsnorm_adaln_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, vp, vp, vp, vp,
+                                            vp, sz, vp]
+    lib.aeris_rmsnorm_adaln_bwd.restype = ctypes.c_int
+    lib.aeris_gate_residual_fwd.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp]
+    lib.aeris_gate_residual_fwd.restype = ctypes.c_int
+    lib.aeris_gate_residual_bwd_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.aeris_gate_residual_bwd_workspace_bytes.restype = sz
+    lib.aeris_gate_residual_bwd.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp, vp, sz, vp]
+    lib.aeris_gate_residual_bwd.restype = ctypes.c_int
+    lib.aeris_swiglu_fwd.argtypes = [vp, i64, i32, vp, vp]
+    lib.aeris_swiglu_fwd.restype = ctypes.c_int
+    lib.aeris_swiglu_bwd.argtypes = [vp, vp, i64, i32, vp, vp]
+    lib.aeris_swiglu_bwd.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -310,3 +333,137 @@ def aeris_mfma_loop_probe(blocks, iters, random_operands, sink):
     if rc != 0:
         raise AerisError(rc, "aeris_mfma_loop_probe")
     return blocks * 4 * iters * 8 * 32768.0
+
+
+# ---------------------------------------------------------------------------------------------
+# include/aeris_layer_ops.h: element-wise operations of a transformer layer.  Activations are
+# contiguous bf16 CUDA tensors [n_rows, channels]; w, alpha, beta, gamma are fp32.
+# ---------------------------------------------------------------------------------------------
+def _rows(t):
+    import torch
+    assert t.is_cuda and t.is_contiguous() and t.dtype == torch.bfloat16 and t.dim() == 2
+    return t.shape[0], t.shape[1]
+
+
+def _f32(*ts):
+    import torch
+    for t in ts:
+        assert t is None or (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32)
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def aeris_rmsnorm_adaln_fwd(x, w, gamma, beta, eps, rows_per_sample, h=None, r=None,
+                            want_r=True):
+    """Returns (h, r): h = RMSNorm(x; w) * (1 + gamma_b) + beta_b, r the reciprocal RMS per row."""
+    import torch
+    n, c = _rows(x)
+    _f32(w, gamma, beta, r)
+    if h is None:
+        h = torch.empty_like(x)
+    if r is None and want_r:
+        r = torch.empty(n, dtype=torch.float32, device=x.device)
+    rc = load().aeris_rmsnorm_adaln_fwd(x.data_ptr(), w.data_ptr(), gamma.data_ptr(),
+                                        beta.data_ptr(), float(eps), n, rows_per_sample, c,
+                                        h.data_ptr(), _ptr(r), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_rmsnorm_adaln_fwd")
+    return h, r
+
+
+def aeris_rmsnorm_adaln_bwd_workspace_bytes(n_rows, rows_per_sample, channels):
+    return load().aeris_rmsnorm_adaln_bwd_workspace_bytes(n_rows, rows_per_sample, channels)
+
+
+def aeris_rmsnorm_adaln_bwd(x, w, gamma, r, dh, rows_per_sample, workspace=None,
+                            want=(True, True, True)):
+    """Returns (dx, dw, dgamma, dbeta); entries of `want` switch dw, dgamma, dbeta off (None)."""
+    import torch
+    n, c = _rows(x)
+    assert _rows(dh) == (n, c)
+    _f32(w, gamma, r)
+    nb = n // rows_per_sample
+    dx = torch.empty_like(x)
+    dw = torch.empty(c, dtype=torch.float32, device=x.device) if want[0] else None
+    dgamma = torch.empty(nb, c, dtype=torch.float32, device=x.device) if want[1] else None
+    dbeta = torch.empty(nb, c, dtype=torch.float32, device=x.device) if want[2] else None
+    if workspace is None:
+        need = aeris_rmsnorm_adaln_bwd_workspace_bytes(n, rows_per_sample, c)
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    rc = load().aeris_rmsnorm_adaln_bwd(x.data_ptr(), w.data_ptr(), gamma.data_ptr(),
+                                        r.data_ptr(), dh.data_ptr(), n, rows_per_sample, c,
+                                        dx.data_ptr(), _ptr(dw), _ptr(dgamma), _ptr(dbeta),
+                                        workspace.data_ptr(), workspace.numel(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_rmsnorm_adaln_bwd")
+    return dx, dw, dgamma, dbeta
+
+
+def aeris_gate_residual_fwd(x, y, alpha, rows_per_sample, out=None):
+    """out = x + alpha_b * y (out may be x or y)."""
+    import torch
+    n, c = _rows(x)
+    assert _rows(y) == (n, c)
+    _f32(alpha)
+    if out is None:
+        out = torch.empty_like(x)
+    rc = load().aeris_gate_residual_fwd(x.data_ptr(), y.data_ptr(), alpha.data_ptr(), n,
+                                        rows_per_sample, c, out.data_ptr(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_gate_residual_fwd")
+    return out
+
+
+def aeris_gate_residual_bwd_workspace_bytes(n_rows, rows_per_sample, channels):
+    return load().aeris_gate_residual_bwd_workspace_bytes(n_rows, rows_per_sample, channels)
+
+
+def aeris_gate_residual_bwd(y, alpha, dout, rows_per_sample, dy=None, workspace=None,
+                            want_dalpha=True):
+    """Returns (dy, dalpha) for out = x + alpha_b * y (dy may be dout)."""
+    import torch
+    n, c = _rows(y)
+    assert _rows(dout) == (n, c)
+    _f32(alpha)
+    if dy is None:
+        dy = torch.empty_like(y)
+    dalpha = (torch.empty(n // rows_per_sample, c, dtype=torch.float32, device=y.device)
+              if want_dalpha else None)
+    if workspace is None:
+        need = aeris_gate_residual_bwd_workspace_bytes(n, rows_per_sample, c)
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=y.device)
+    rc = load().aeris_gate_residual_bwd(y.data_ptr(), alpha.data_ptr(), dout.data_ptr(), n,
+                                        rows_per_sample, c, dy.data_ptr(), _ptr(dalpha),
+                                        workspace.data_ptr(), workspace.numel(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_gate_residual_bwd")
+    return dy, dalpha
+
+
+def aeris_swiglu_fwd(uv, g=None):
+    """g = silu(u) * v for uv = [u | v]."""
+    import torch
+    n, c2 = _rows(uv)
+    assert c2 % 2 == 0
+    if g is None:
+        g = torch.empty(n, c2 // 2, dtype=torch.bfloat16, device=uv.device)
+    rc = load().aeris_swiglu_fwd(uv.data_ptr(), n, c2 // 2, g.data_ptr(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_swiglu_fwd")
+    return g
+
+
+def aeris_swiglu_bwd(uv, dg, duv=None):
+    """duv = [du | dv] (duv may be uv)."""
+    import torch
+    n, c2 = _rows(uv)
+    assert _rows(dg) == (n, c2 // 2)
+    if duv is None:
+        duv = torch.empty_like(uv)
+    rc = load().aeris_swiglu_bwd(uv.data_ptr(), dg.data_ptr(), n, c2 // 2, duv.data_ptr(),
+                                 _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_swiglu_bwd")
+    return duv

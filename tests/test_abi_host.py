@@ -12,9 +12,11 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_exports_match_header():
-    text = open(os.path.join(ROOT, "include", "aeris_winattn.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(aeris_[a-z0-9_]+)\s*\(", text))
+    declared = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        declared |= set(re.findall(r"\b(aeris_[a-z0-9_]+)\s*\(", text))
     assert declared == set(B.EXPORTS)
     lib = B.load()
     for name in declared:
@@ -141,3 +143,44 @@ def test_header_is_plain_c_and_callable_from_c(tmp_path):
     assert int(got["bwd_ws"]) == 2 * (1 * 128 * 4 * 64 + 64) * 4
     assert int(got["rope_fwd_ws"]) == 64 * 128 * 4 * 32 * 2
     assert got["null_fwd"] == "-1" and got["null_rope"] == "-1"
+
+
+# ------------------------------------------------------------------ include/aeris_layer_ops.h
+def test_layer_ops_reject_bad_arguments_before_launching():
+    lib = B.load()
+    a = ctypes.c_void_p(4096)          # a non-null, aligned address that is never dereferenced
+    odd = ctypes.c_void_p(4096 + 8)
+    ok = (a, a, a, a, 1e-6, 8, 4, 64, a, a, None)
+    assert lib.aeris_rmsnorm_adaln_fwd(None, a, a, a, 1e-6, 8, 4, 64, a, a, None) == -1
+    assert lib.aeris_rmsnorm_adaln_fwd(a, a, a, a, 1e-6, 8, 4, 64, None, a, None) == -1
+    assert lib.aeris_rmsnorm_adaln_fwd(a, a, a, a, 1e-6, 0, 4, 64, a, a, None) == -2
+    assert lib.aeris_rmsnorm_adaln_fwd(a, a, a, a, 1e-6, 8, 4, 4104, a, a, None) == -2   # too wide
+    assert lib.aeris_rmsnorm_adaln_fwd(a, a, a, a, 1e-6, 8, 4, 4, a, a, None) == -2      # too narrow
+    assert lib.aeris_rmsnorm_adaln_fwd(a, a, a, a, 1e-6, 8, 4, 60, a, a, None) == -3     # 60 % 8
+    assert lib.aeris_rmsnorm_adaln_fwd(a, a, a, a, 1e-6, 8, 3, 64, a, a, None) == -3     # 8 % 3
+    assert lib.aeris_rmsnorm_adaln_fwd(a, a, a, a, -1.0, 8, 4, 64, a, a, None) == -2
+    assert lib.aeris_rmsnorm_adaln_fwd(odd, a, a, a, 1e-6, 8, 4, 64, a, a, None) == -7
+    assert len(ok) == 11
+    need = lib.aeris_rmsnorm_adaln_bwd_workspace_bytes(8, 4, 64)
+    assert need == 2 * 1 * 2 * 64 * 4           # two samples, one chunk each, two rows of 64 floats
+    assert lib.aeris_rmsnorm_adaln_bwd_workspace_bytes(8, 3, 64) == 0
+    assert lib.aeris_rmsnorm_adaln_bwd(a, a, a, a, a, 8, 4, 64, a, None, None, None, a, need - 1,
+                                       None) == -8
+    assert lib.aeris_rmsnorm_adaln_bwd(a, a, a, a, a, 8, 4, 64, a, None, None, None, None, need,
+                                       None) == -1
+    assert lib.aeris_gate_residual_fwd(a, None, a, 8, 4, 64, a, None) == -1
+    assert lib.aeris_gate_residual_fwd(a, a, a, 8, 4, 64, odd, None) == -7
+    assert lib.aeris_gate_residual_bwd_workspace_bytes(8, 4, 64) == 2 * 64 * 4
+    assert lib.aeris_gate_residual_bwd(a, a, a, 8, 4, 64, a, None, a, 8, None) == -8
+    assert lib.aeris_swiglu_fwd(a, 8, 12, a, None) == -3
+    assert lib.aeris_swiglu_fwd(a, 0, 16, a, None) == -2
+    assert lib.aeris_swiglu_fwd(None, 8, 16, a, None) == -1
+    assert lib.aeris_swiglu_bwd(a, odd, 8, 16, a, None) == -7
+
+
+def test_layer_ops_workspace_grows_with_the_number_of_chunks():
+    lib = B.load()
+    # 4 samples of 1,036,800 rows: 512 chunks per sample (2048 workgroups in all)
+    assert lib.aeris_rmsnorm_adaln_bwd_workspace_bytes(4 * 1036800, 1036800, 2048) == 2048 * 2 * 2048 * 4
+    # tiny samples: at most one chunk per four rows
+    assert lib.aeris_gate_residual_bwd_workspace_bytes(6, 6, 8) == 2 * 8 * 4
