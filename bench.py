@@ -70,7 +70,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS) + ["layer_ops"],
+                    help="layer_ops: the element-wise kernels of include/aeris_layer_ops.h on the "
+                         "headline grid's tokens (a bandwidth figure, not the headline metric)")
+    ap.add_argument("--channels", type=int, default=2048, help="row width for --workload layer_ops")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-pairs", type=int, default=64)
     ap.add_argument("--no-mfma-loop", action="store_true",
@@ -91,6 +94,8 @@ def main():
     from paper_2509_13523_amd import synth
 
     B.load()   # fails loudly if the HIP library is not built
+    if args.workload == "layer_ops":
+        return bench_layer_ops(args)
     wl = WORKLOADS[args.workload]
     shape, win, mask = wl["shape"], wl["win"], wl["mask"]
     Bn, H, W, nh, d = shape
@@ -253,6 +258,96 @@ def cpu_baseline(wl, tq, tk, tv, tdo, n_pairs):
             "sample": "%d (batch, window, head) pairs of the workload (interior, seam and corner "
                       "windows), fwd%s, %.1f s of CPU time" %
                       (n_pairs, "+bwd" if tdo is not None else "", secs)}
+
+
+def bench_layer_ops(args):
+    """One step = the six element-wise kernels around the attention of one transformer layer
+    (RMSNorm + modulation forward and backward, gated residual forward and backward, SwiGLU gate
+    forward and backward) on 4 x 720 x 1440 token rows.  Bound by HBM: algorithmic bytes = every
+    activation read once and every result written once."""
+    import numpy as np
+    import torch
+    from paper_2509_13523_amd import binding as B
+    nb, rps, C = 4, 720 * 1440, args.channels
+    n = nb * rps
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    gen = torch.Generator(device=dev).manual_seed(7000)
+    x = torch.randn(n, C, device=dev, dtype=torch.bfloat16, generator=gen)
+    dh = torch.randn(n, C, device=dev, dtype=torch.bfloat16, generator=gen)
+    w = 1.0 + 0.1 * torch.randn(C, device=dev, generator=gen)
+    gamma = 0.3 * torch.randn(nb, C, device=dev, generator=gen)
+    beta = 0.5 * torch.randn(nb, C, device=dev, generator=gen)
+    h, out = torch.empty_like(x), torch.empty_like(x)
+    r = torch.empty(n, dtype=torch.float32, device=dev)
+    g = torch.empty(n, C // 2, dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(B.aeris_rmsnorm_adaln_bwd_workspace_bytes(n, rps, C), dtype=torch.uint8,
+                     device=dev)
+    ops = [   # name, call, algorithmic bytes
+        ("rmsnorm_adaln_fwd", lambda: B.aeris_rmsnorm_adaln_fwd(x, w, gamma, beta, 1e-6, rps, h=h, r=r),
+         4 * n * C + 4 * n),
+        ("rmsnorm_adaln_bwd", lambda: B.aeris_rmsnorm_adaln_bwd(x, w, gamma, r, dh, rps, workspace=ws),
+         6 * n * C + 4 * n),
+        ("gate_residual_fwd", lambda: B.aeris_gate_residual_fwd(x, dh, beta, rps, out=out), 6 * n * C),
+        ("gate_residual_bwd", lambda: B.aeris_gate_residual_bwd(x, beta, dh, rps, dy=out, workspace=ws),
+         6 * n * C),
+        ("swiglu_fwd", lambda: B.aeris_swiglu_fwd(x, g=g), 3 * n * C),
+        ("swiglu_bwd", lambda: B.aeris_swiglu_bwd(x, g, duv=out), 5 * n * C),
+    ]
+    for _ in range(args.warmup):
+        for _, fn, _ in ops:
+            fn()
+    torch.cuda.synchronize()
+    ev = {name: [] for name, _, _ in ops}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        for name, fn, _ in ops:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            ev[name].append((e0, e1))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = {name: sum(a.elapsed_time(b) for a, b in ev[name]) / args.steps for name in ev}
+    total_bytes = sum(b for _, _, b in ops)
+    step_ms = wall * 1e3 / args.steps
+    per_kernel = {name: {"ms": round(ms[name], 3), "GBps": round(b / ms[name] / 1e6, 1)}
+                  for name, _, b in ops}
+    slow = max(ops, key=lambda o: ms[o[0]])
+    achieved = slow[2] / ms[slow[0]] / 1e6
+    result = {"metric": "layer_ops_algorithmic_bandwidth", "value": round(total_bytes / step_ms / 1e6, 1),
+              "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+              "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak",
+              "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+              "config": {"workload": "layer_ops: %d x %d token rows x %d channels (bf16), SwiGLU "
+                                     "hidden %d" % (nb, rps, C, C // 2), "kernels": per_kernel},
+              "roofline": {"bound": "hbm", "kernel": slow[0], "achieved": round(achieved, 1),
+                           "peak": 8000.0, "unit": "GB/s", "frac": round(achieved / 8000.0, 4),
+                           "traffic": None}}
+    if not args.no_cpu_baseline:
+        from oracle import block_oracle as bo
+        rows = 4096
+        x64 = x[:rows].float().cpu().numpy().astype(np.float64)
+        g64 = dh[:rows].float().cpu().numpy().astype(np.float64)
+        w64 = w.cpu().numpy().astype(np.float64)
+        gm, bt = gamma[:1].cpu().numpy().astype(np.float64), beta[:1].cpu().numpy().astype(np.float64)
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            bo.rmsnorm_adaln_fwd(x64, w64, gm, bt, 1e-6, rows)
+            bo.rmsnorm_adaln_bwd(x64, w64, gm, bt, 1e-6, rows, g64)
+            bo.gate_residual_fwd(x64, g64, bt, rows)
+            bo.gate_residual_bwd(x64, bt, g64, rows)
+            bo.swiglu_fwd(x64)
+            bo.swiglu_bwd(x64, g64[:, :C // 2])
+            reps += 1
+        secs = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": round(total_bytes * (rows / n) * reps / secs / 1e9, 3),
+                                  "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                  "sample": "%d rows, %d passes of the six operations, %.1f s; counted "
+                                            "in the kernels' algorithmic (bf16) bytes" % (rows, reps, secs)}
+    print(json.dumps(result))
 
 
 if __name__ == "__main__":
