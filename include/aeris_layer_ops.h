@@ -18,7 +18,8 @@
  * reproducible from call to call.
  *
  * Limits: channels % 8 == 0 and 8 <= channels <= AERIS_MAX_CHANNELS; hidden % 8 == 0;
- * n_rows % rows_per_sample == 0.  Pointers are DEVICE pointers, 16-byte aligned, owned by the
+ * n_rows % rows_per_sample == 0 and at most 2^20 samples (AERIS_ERR_INVALID_SHAPE /
+ * AERIS_ERR_NOT_DIVISIBLE otherwise).  Pointers are DEVICE pointers, 16-byte aligned, owned by the
  * caller; inputs are read-only and outputs fully overwritten.  The library allocates nothing and
  * never synchronises: calls only enqueue kernels on `hip_stream` (a hipStream_t passed as
  * void*; NULL is the default stream).  Errors are the AERIS_ERR_* codes of aeris_winattn.h;
