@@ -177,3 +177,42 @@ def test_rope_seeded_sweep_of_small_shapes():
         print("case", case, shape, (wh, ww), (sh, sw), mask, mode, base, out, flush=True)
         run_rope_case(shape, (wh, ww), (sh, sw), mask, mode, base=base, seed=7100 + case,
                       outs=(out,))
+
+
+def test_rope_attention_on_packed_qkv_is_bitwise_the_contiguous_result():
+    """Queries, keys and values interleaved per token, as a fused QKV projection writes them
+    ([B,H,W,3,heads,d]), gradients written into the same packing: the rotary entry points must
+    give exactly what they give on separate contiguous tensors (which the cases above hold to the
+    oracle)."""
+    import ctypes
+    shape, win, shift, mask = (2, 24, 36, 3, 64), (12, 12), (6, 6), B.AERIS_MASK_SWIN
+    Bn, H, W, nh, d = shape
+    bits = synth.make_inputs("normal", 4300, shape, 4)
+    tq, tk, tv, tdo = [to_dev(b) for b in bits]
+    mode = B.AERIS_ROPE_POS_WINDOW
+    o_ref, lse_ref = B.aeris_winattn_rope_fwd(tq, tk, tv, win, shift, 100.0, mode, mask)
+    dq_ref, dk_ref, dv_ref = B.aeris_winattn_rope_bwd(tq, tk, tv, o_ref, lse_ref, tdo, win, shift,
+                                                      100.0, mode, mask)
+    packed = torch.stack([tq, tk, tv], dim=3).contiguous()
+    dpacked = torch.full_like(packed, float("nan"))
+    o = torch.empty_like(tq)
+    lse = torch.empty_like(lse_ref)
+    p = B.make_params(shape, win, shift, mask, qkv_strides=(3 * nh * d, d))
+    r = B.aeris_rope_params(100.0, mode)
+    lib = B.load()
+    ptr = lambda t, i: t.data_ptr() + i * nh * d * 2
+    stream = torch.cuda.current_stream().cuda_stream
+    ws = torch.empty(B.aeris_winattn_rope_bwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    rc = lib.aeris_winattn_rope_fwd(ctypes.byref(p), ctypes.byref(r), ptr(packed, 0), ptr(packed, 1),
+                                    ptr(packed, 2), o.data_ptr(), lse.data_ptr(), ws.data_ptr(),
+                                    ws.numel(), stream)
+    assert rc == 0
+    rc = lib.aeris_winattn_rope_bwd(ctypes.byref(p), ctypes.byref(r), ptr(packed, 0), ptr(packed, 1),
+                                    ptr(packed, 2), o.data_ptr(), lse.data_ptr(), tdo.data_ptr(),
+                                    ptr(dpacked, 0), ptr(dpacked, 1), ptr(dpacked, 2), ws.data_ptr(),
+                                    ws.numel(), stream)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert torch.equal(o, o_ref) and torch.equal(lse, lse_ref)
+    for i, ref in enumerate((dq_ref, dk_ref, dv_ref)):
+        assert torch.equal(dpacked[:, :, :, i].contiguous().view(torch.int16), ref.view(torch.int16))
