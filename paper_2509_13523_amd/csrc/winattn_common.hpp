@@ -31,6 +31,7 @@ constexpr int kWaves = 4;
 constexpr int kResident = 128;     // tokens a workgroup keeps in registers (32 per wave)
 constexpr int kStream = 64;        // tokens per streamed LDS tile
 constexpr float kLazyRescale = 8.0f;  // log2 units a row maximum may lag behind
+constexpr float kSumLimit = 4096.0f;  // a lane's 16 exponentials of a block may add up to this
 constexpr float kLog2e = 1.4426950408889634f;
 
 // Host-filled launch parameters (plain data, passed by value).

@@ -147,13 +147,29 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
         if (kidx < lo_q || kidx >= hi_q) sacc[i] = -INFINITY;
       }
     }
-    // online softmax, log2 domain, lagging maximum
-    float mx = sacc[0];
+    // online softmax, log2 domain, lagging maximum.  The reference point m_run only has to keep
+    // the exponentials in range, so the common case computes them straight away and looks at
+    // their sum: 16 values that add up to at most 2^12 are each at most 2^12.  Only when a lane's
+    // sum is larger (or not a number), or a row has no reference point yet (its first block with
+    // a visible key sets it to that block's maximum, so that a row of very negative logits does
+    // not underflow), is the row maximum taken and the reference point raised, for both lanes of
+    // a query alike, and the block's exponentials computed again.
+    float pv[16];
+    float psum = 0.f;   // in fp32 over the unrounded probabilities: the saved LSE stays exact
+    {
+      const float m_sub = m_run == -INFINITY ? 0.f : m_run;
 #pragma unroll
-    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sacc[i]);
-    mx = wave_half_max(mx) * p.scale_log2;
-    const bool grow = mx > m_run + kLazyRescale;
-    if (__builtin_expect(__any(grow), 0)) {
+      for (int i = 0; i < 16; ++i) {
+        pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], p.scale_log2, -m_sub));
+        psum += pv[i];
+      }
+    }
+    if (__builtin_expect(__any(!(psum <= kSumLimit) || m_run == -INFINITY), 0)) {
+      float mx = sacc[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sacc[i]);
+      mx = wave_half_max(mx) * p.scale_log2;
+      const bool grow = mx > m_run + kLazyRescale;
       const float alpha = grow ? __builtin_amdgcn_exp2f(m_run - mx) : 1.f;
       m_run = grow ? mx : m_run;
       l_run *= alpha;
@@ -161,14 +177,13 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
       for (int cb = 0; cb < D / 32; ++cb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[cb][i] *= alpha;
-    }
-    const float m_sub = m_run == -INFINITY ? 0.f : m_run;
-    float pv[16];
-    float psum = 0.f;   // in fp32 over the unrounded probabilities: the saved LSE stays exact
+      const float m_sub = m_run == -INFINITY ? 0.f : m_run;
+      psum = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], p.scale_log2, -m_sub));
-      psum += pv[i];
+      for (int i = 0; i < 16; ++i) {
+        pv[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], p.scale_log2, -m_sub));
+        psum += pv[i];
+      }
     }
     l_run += psum;
 #pragma unroll
