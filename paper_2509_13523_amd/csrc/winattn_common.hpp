@@ -164,17 +164,19 @@ struct Ranges {
   int lo_max, hi_min; // intersection over the wave (blocks inside need no mask)
   int wg_lo, wg_hi;   // union over the workgroup (loop bounds)
 
-  __device__ __forceinline__ void init(const Window& win, int tile, int wave, int qi) {
+  // resident: tokens a workgroup keeps in registers (32 per wave)
+  __device__ __forceinline__ void init(const Window& win, int tile, int wave, int qi,
+                                       int resident = kResident) {
     const int T = win.T;
-    const int wave_t0 = tile * kResident + wave * 32;
+    const int wave_t0 = tile * resident + wave * 32;
     wave_active = wave_t0 < T;
     const int t = wave_t0 + qi;
     valid = t < T;
     tok = valid ? t : T - 1;
     win.range(tok, lo, hi);
     int unused;
-    const int wg_last = tile * kResident + kResident - 1;
-    win.range(tile * kResident, wg_lo, unused);
+    const int wg_last = tile * resident + resident - 1;
+    win.range(tile * resident, wg_lo, unused);
     win.range(wg_last < T ? wg_last : T - 1, unused, wg_hi);
     w_lo = w_hi = lo_max = hi_min = 0;
     if (wave_active) {
@@ -201,7 +203,7 @@ struct Ranges {
 __device__ __forceinline__ void build_token_table(const KParams& p, const Window& win,
                                                   int* tok_grid) {
   const int padded = table_bytes(p.T) / 4;
-  for (int t = threadIdx.x; t < padded; t += kThreads)
+  for (int t = threadIdx.x; t < padded; t += blockDim.x)
     tok_grid[t] = win.grid_index(p, t < p.T ? t : p.T - 1);
 }
 
@@ -398,13 +400,15 @@ __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0
 #define AERIS_TICK_FLUSH(array)
 #endif
 
-template <int D>
+// W: wavefronts of the workgroup (they share the filling of a tile).
+template <int D, int W = kWaves>
 struct Tile {
   static constexpr int NC = D / 8;                  // 16-byte chunks per token row
   static constexpr int kBytes = kStream * D * 2;
   static constexpr int kSubBytes = 32 * D * 2;      // 32-token sub-block
   static constexpr int kGroupBytes = 16 * D * 2;    // 16-token group of a second product
-  static constexpr int kFillPerWave = NC / kWaves;  // wave instructions per tile and wave
+  static constexpr int kFillPerWave = NC / W;       // wave instructions per tile and wave
+  static_assert(NC % W == 0, "every wave must issue a whole number of copies per tile");
 
   __device__ __forceinline__ static int swz(int r) {
     if (D == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
@@ -418,7 +422,7 @@ struct Tile {
 
   // Asynchronous tile fill.  A wave instruction moves 64 chunks = kRowsPerInst token
   // rows.  Instruction i of wave w covers rows
-  //   i * kRowStep + w * kRowsPerInst + lane / NC,      kRowStep = kRowsPerInst * kWaves,
+  //   i * kRowStep + w * kRowsPerInst + lane / NC,      kRowStep = kRowsPerInst * W,
   // and because swz() has period 16 (which divides kRowStep) the lane's source chunk is
   // the same in every instruction: per 16 bytes moved the source is
   //   src + table[t0 + row_i] * stride_bytes
@@ -429,7 +433,7 @@ struct Tile {
   // registers; Filler::issue_one()/issue() launch the copies of one tensor.  Tensors
   // streamed together (K and V, or Q and dO) share one Rows.
   static constexpr int kRowsPerInst = 64 / NC;
-  static constexpr int kRowStep = kRowsPerInst * kWaves;
+  static constexpr int kRowStep = kRowsPerInst * W;
   static constexpr int kInstStep = kRowStep * D * 2;   // LDS bytes between instructions
   static_assert(kRowStep % 16 == 0, "swizzle period must divide the instruction row step");
   struct Rows {

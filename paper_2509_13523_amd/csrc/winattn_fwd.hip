@@ -27,11 +27,15 @@ constexpr size_t fwd_smem_bytes(int T) {
   return table_bytes(T) + 4 * Tile<D>::kBytes;   // table + 2 buffers x (K, V)
 }
 
-template <int D, typename OutT>
-__global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
+// W wavefronts per workgroup, 32 resident queries each.  Four waves (two workgroups per CU, so
+// one's prologue and epilogue run under the other's loop) suit short windows; eight waves (one
+// workgroup per CU) stream every K/V tile for twice as many queries, which halves the
+// L2 -> LDS traffic and the copy instructions per product and wins once the loop is long.
+template <int D, typename OutT, int W>
+__global__ __launch_bounds__(W * 64, W == 4 ? 2 : 1) void winattn_fwd_kernel(
     KParams p, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
     const bf16_t* __restrict__ v, OutT* __restrict__ o, float* __restrict__ lse) {
-  using Tl = Tile<D>;
+  using Tl = Tile<D, W>;
   constexpr uint32_t kBuf = 2 * Tl::kBytes;   // one buffer: K tile, V tile
   extern __shared__ __align__(16) unsigned char smem[];
   int* tok_grid = reinterpret_cast<int*>(smem);
@@ -57,7 +61,7 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
 
   // ---- this lane's query ----------------------------------------------------
   Ranges rg;
-  rg.init(win, qt, wave, qi);
+  rg.init(win, qt, wave, qi, W * 32);
   const int q_grid = tok_grid[rg.tok];
   const int lo_q = rg.lo, hi_q = rg.hi;
 
@@ -295,17 +299,30 @@ __global__ __launch_bounds__(kThreads, 2) void winattn_fwd_kernel(
         (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
 }
 
-template <int D, typename OutT>
-static int launch_fwd_t(const KParams& kp, const void* q, const void* k, const void* v, void* o,
+// Windows of at least this many tokens run with eight waves per workgroup (head_dim >= 64).
+constexpr int kWideFromTokens = 2048;
+
+template <int D, typename OutT, int W>
+static int launch_fwd_w(KParams kp, const void* q, const void* k, const void* v, void* o,
                         float* lse, hipStream_t stream) {
+  kp.n_tiles = (kp.T + W * 32 - 1) / (W * 32);
   const int n_blocks = grid_blocks(kp);
   const size_t smem = fwd_smem_bytes<D>(kp.T);
-  auto kern = winattn_fwd_kernel<D, OutT>;
-  if (!allow_full_lds<winattn_fwd_kernel<D, OutT>>()) return -1;
-  hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp,
+  auto kern = winattn_fwd_kernel<D, OutT, W>;
+  if (!allow_full_lds<winattn_fwd_kernel<D, OutT, W>>()) return -1;
+  hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(W * 64), smem, stream, kp,
                      static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
                      static_cast<const bf16_t*>(v), static_cast<OutT*>(o), lse);
   return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+template <int D, typename OutT>
+static int launch_fwd_t(const KParams& kp, const void* q, const void* k, const void* v, void* o,
+                        float* lse, hipStream_t stream) {
+  if constexpr (D >= 64) {
+    if (kp.T >= kWideFromTokens) return launch_fwd_w<D, OutT, 8>(kp, q, k, v, o, lse, stream);
+  }
+  return launch_fwd_w<D, OutT, 4>(kp, q, k, v, o, lse, stream);
 }
 
 int launch_fwd(const KParams& kp, int head_dim, bool out_f32, const void* q, const void* k,
