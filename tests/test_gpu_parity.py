@@ -177,6 +177,16 @@ def test_paper_window_60x60(d):
              outs=(B.AERIS_DT_BF16,))
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_windows_between_the_narrow_and_wide_forward_tiles(d):
+    # T = 2500 (50x50): forward tiles of 256 queries with a ragged tenth tile of 196;
+    # T = 2025 (45x45) stays on tiles of 128
+    run_case((1, 50, 100, 1, d), (50, 50), (25, 25), B.AERIS_MASK_SWIN, seed=93,
+             outs=(B.AERIS_DT_BF16,))
+    run_case((1, 45, 45, 1, d), (45, 45), (20, 11), B.AERIS_MASK_LAT, seed=94, bwd=False,
+             outs=(B.AERIS_DT_F32,))
+
+
 def test_config5_unshifted_layer_fwd_bwd_sampled():
     # the other layer of the bench step: shift 0 (no seam, no mask effect)
     samples = [(1, 0, 0, 3), (2, 6, 17, 12)]
