@@ -50,7 +50,7 @@ WORKLOADS = {
 # HBM traffic per launch, bytes, from two rocprofv3 --pmc runs of this file (FETCH_SIZE, then
 # WRITE_SIZE, each scaled by what the same counter reads for the --calibrate-copy kernels:
 # factors 2.000 and 1.000); profiles/c5_kernels_and_counters.txt has the commands and numbers.
-MEASURED_TRAFFIC = {("c5", "fwd"): 71.4e9, ("c5", "dq"): 107.8e9, ("c5", "dkdv"): 114.2e9}
+MEASURED_TRAFFIC = {("c5", "fwd"): 74.6e9, ("c5", "dq"): 110.3e9, ("c5", "dkdv"): 113.6e9}
 
 
 def unmasked_pairs(H, W, win, shift, mask):
