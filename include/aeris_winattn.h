@@ -218,6 +218,22 @@ int aeris_winattn_rope_bwd(const aeris_winattn_params* p, const aeris_rope_param
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The two calls above for a listed subset of the windows (SWiPe: a rank's share of the windows
+ * runs the same rotary attention): `windows`, `n_windows` as in aeris_winattn_fwd_windows.  Only
+ * tokens of the listed windows are rotated, read or written; the workspace has the size of the
+ * full-grid calls (the rotated copies keep the full-grid layout).
+ */
+int aeris_winattn_rope_fwd_windows(const aeris_winattn_params* p, const aeris_rope_params* r,
+                                   const int32_t* windows, int32_t n_windows, const void* q,
+                                   const void* k, const void* v, void* o, float* lse,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+int aeris_winattn_rope_bwd_windows(const aeris_winattn_params* p, const aeris_rope_params* r,
+                                   const int32_t* windows, int32_t n_windows, const void* q,
+                                   const void* k, const void* v, const void* o, const float* lse,
+                                   const void* d_o, void* dq, void* dk, void* dv, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream);
+
+/*
  * Measurement aid (for callers that report a fraction of the attainable MFMA rate; not part
  * of the attention path): launches `blocks` workgroups of 256 threads, each wave issuing
  * 8 * iters v_mfma_f32_32x32x16_bf16 on register operands (32768 FLOP each) and nothing else.

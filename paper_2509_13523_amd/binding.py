@@ -21,7 +21,8 @@ EXPORTS = ("aeris_winattn_fwd", "aeris_winattn_bwd", "aeris_winattn_bwd_stages",
            "aeris_winattn_fwd_windows", "aeris_winattn_bwd_windows",
            "aeris_mfma_loop_probe", "aeris_rope2d_apply", "aeris_winattn_rope_fwd_workspace_bytes",
            "aeris_winattn_rope_bwd_workspace_bytes", "aeris_winattn_rope_fwd",
-           "aeris_winattn_rope_bwd",
+           "aeris_winattn_rope_bwd", "aeris_winattn_rope_fwd_windows",
+           "aeris_winattn_rope_bwd_windows",
            # include/aeris_layer_ops.h
            "aeris_rmsnorm_adaln_fwd", "aeris_rmsnorm_adaln_bwd_workspace_bytes",
            "aeris_rmsnorm_adaln_bwd", "aeris_gate_residual_fwd",
@@ -100,6 +101,12 @@ def load():
     lib.aeris_winattn_rope_bwd.argtypes = [P, R, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                            ctypes.c_size_t, vp]
     lib.aeris_winattn_rope_bwd.restype = ctypes.c_int
+    lib.aeris_winattn_rope_fwd_windows.argtypes = [P, R, vp, ctypes.c_int32, vp, vp, vp, vp, vp, vp,
+                                                   ctypes.c_size_t, vp]
+    lib.aeris_winattn_rope_fwd_windows.restype = ctypes.c_int
+    lib.aeris_winattn_rope_bwd_windows.argtypes = [P, R, vp, ctypes.c_int32, vp, vp, vp, vp, vp, vp,
+                                                   vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.aeris_winattn_rope_bwd_windows.restype = ctypes.c_int
     i64, i32, f32, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
     lib.aeris_rmsnorm_adaln_fwd.argtypes = [vp, vp, vp, vp, f32, i64, i64, i32, vp, vp, vp]
     lib.aeris_rmsnorm_adaln_fwd.restype = ctypes.c_int
@@ -321,6 +328,50 @@ def aeris_winattn_bwd_windows(q, k, v, o, lse, d_o, win, shift, windows, dq, dk,
                                           workspace.numel(), _stream())
     if rc != 0:
         raise AerisError(rc, "aeris_winattn_bwd_windows")
+    return dq, dk, dv
+
+
+def aeris_winattn_rope_fwd_windows(q, k, v, win, shift, base, positions, windows, o, lse,
+                                   mask=AERIS_MASK_NONE, scale=None, out_dtype=AERIS_DT_BF16,
+                                   workspace=None):
+    """Rotary attention over the listed windows only; o and lse are written only inside them."""
+    import torch
+    assert windows.is_cuda and windows.dtype == torch.int32 and windows.is_contiguous()
+    for t in (q, k, v):
+        assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and t.shape == q.shape
+    p = make_params(q.shape, win, shift, mask, scale, out_dtype)
+    r = aeris_rope_params(float(base), int(positions))
+    if workspace is None:
+        workspace = torch.empty(aeris_winattn_rope_fwd_workspace_bytes(p), dtype=torch.uint8,
+                                device=q.device)
+    rc = load().aeris_winattn_rope_fwd_windows(ctypes.byref(p), ctypes.byref(r), windows.data_ptr(),
+                                               windows.numel(), q.data_ptr(), k.data_ptr(),
+                                               v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                               workspace.data_ptr(), workspace.numel(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_winattn_rope_fwd_windows")
+    return o, lse
+
+
+def aeris_winattn_rope_bwd_windows(q, k, v, o, lse, d_o, win, shift, base, positions, windows,
+                                   dq, dk, dv, mask=AERIS_MASK_NONE, scale=None,
+                                   out_dtype=AERIS_DT_BF16, workspace=None):
+    """Backward of the call above; dq, dk, dv are written only inside the listed windows."""
+    import torch
+    assert windows.is_cuda and windows.dtype == torch.int32 and windows.is_contiguous()
+    p = make_params(q.shape, win, shift, mask, scale, out_dtype)
+    r = aeris_rope_params(float(base), int(positions))
+    if workspace is None:
+        workspace = torch.empty(aeris_winattn_rope_bwd_workspace_bytes(p), dtype=torch.uint8,
+                                device=q.device)
+    rc = load().aeris_winattn_rope_bwd_windows(ctypes.byref(p), ctypes.byref(r), windows.data_ptr(),
+                                               windows.numel(), q.data_ptr(), k.data_ptr(),
+                                               v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                                               d_o.data_ptr(), dq.data_ptr(), dk.data_ptr(),
+                                               dv.data_ptr(), workspace.data_ptr(),
+                                               workspace.numel(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_winattn_rope_bwd_windows")
     return dq, dk, dv
 
 

@@ -234,9 +234,11 @@ size_t aeris_winattn_rope_bwd_workspace_bytes(const aeris_winattn_params* p) {
   return 2 * dense_tensor_bytes(p) + aeris::bwd_workspace_bytes(derive(p, s));
 }
 
-int aeris_winattn_rope_fwd(const aeris_winattn_params* p, const aeris_rope_params* r,
-                           const void* q, const void* k, const void* v, void* o, float* lse,
-                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+// windows == nullptr: all windows
+static int rope_fwd_impl(const aeris_winattn_params* p, const aeris_rope_params* r,
+                         const int32_t* windows, int32_t n_windows, bool listed, const void* q,
+                         const void* k, const void* v, void* o, float* lse, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
   Strides s;
   int rc = resolve(p, &s);
   if (rc != AERIS_OK) return rc;
@@ -247,6 +249,10 @@ int aeris_winattn_rope_fwd(const aeris_winattn_params* p, const aeris_rope_param
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) ||
       misaligned(workspace))
     return AERIS_ERR_MISALIGNED;
+  if (listed) {
+    rc = restrict_windows(&kp, windows, n_windows);
+    if (rc != AERIS_OK) return rc;
+  }
   if (workspace_bytes < aeris_winattn_rope_fwd_workspace_bytes(p))
     return AERIS_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -263,10 +269,11 @@ int aeris_winattn_rope_fwd(const aeris_winattn_params* p, const aeris_rope_param
   return AERIS_OK;
 }
 
-int aeris_winattn_rope_bwd(const aeris_winattn_params* p, const aeris_rope_params* r,
-                           const void* q, const void* k, const void* v, const void* o,
-                           const float* lse, const void* d_o, void* dq, void* dk, void* dv,
-                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+static int rope_bwd_impl(const aeris_winattn_params* p, const aeris_rope_params* r,
+                         const int32_t* windows, int32_t n_windows, bool listed, const void* q,
+                         const void* k, const void* v, const void* o, const float* lse,
+                         const void* d_o, void* dq, void* dk, void* dv, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
   Strides s;
   int rc = resolve(p, &s);
   if (rc != AERIS_OK) return rc;
@@ -279,6 +286,10 @@ int aeris_winattn_rope_bwd(const aeris_winattn_params* p, const aeris_rope_param
       misaligned(d_o) || misaligned(dq) || misaligned(dk) || misaligned(dv) ||
       misaligned(workspace))
     return AERIS_ERR_MISALIGNED;
+  if (listed) {
+    rc = restrict_windows(&kp, windows, n_windows);
+    if (rc != AERIS_OK) return rc;
+  }
   if (workspace_bytes < aeris_winattn_rope_bwd_workspace_bytes(p))
     return AERIS_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -300,6 +311,38 @@ int aeris_winattn_rope_bwd(const aeris_winattn_params* p, const aeris_rope_param
                         d_o, dq, dk, dv, stats, stream, AERIS_BWD_ALL) != 0)
     return AERIS_ERR_HIP_LAUNCH;
   return AERIS_OK;
+}
+
+int aeris_winattn_rope_fwd(const aeris_winattn_params* p, const aeris_rope_params* r,
+                           const void* q, const void* k, const void* v, void* o, float* lse,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return rope_fwd_impl(p, r, nullptr, 0, false, q, k, v, o, lse, workspace, workspace_bytes,
+                       hip_stream);
+}
+
+int aeris_winattn_rope_bwd(const aeris_winattn_params* p, const aeris_rope_params* r,
+                           const void* q, const void* k, const void* v, const void* o,
+                           const float* lse, const void* d_o, void* dq, void* dk, void* dv,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return rope_bwd_impl(p, r, nullptr, 0, false, q, k, v, o, lse, d_o, dq, dk, dv, workspace,
+                       workspace_bytes, hip_stream);
+}
+
+int aeris_winattn_rope_fwd_windows(const aeris_winattn_params* p, const aeris_rope_params* r,
+                                   const int32_t* windows, int32_t n_windows, const void* q,
+                                   const void* k, const void* v, void* o, float* lse,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return rope_fwd_impl(p, r, windows, n_windows, true, q, k, v, o, lse, workspace,
+                       workspace_bytes, hip_stream);
+}
+
+int aeris_winattn_rope_bwd_windows(const aeris_winattn_params* p, const aeris_rope_params* r,
+                                   const int32_t* windows, int32_t n_windows, const void* q,
+                                   const void* k, const void* v, const void* o, const float* lse,
+                                   const void* d_o, void* dq, void* dk, void* dv, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream) {
+  return rope_bwd_impl(p, r, windows, n_windows, true, q, k, v, o, lse, d_o, dq, dk, dv,
+                       workspace, workspace_bytes, hip_stream);
 }
 
 int aeris_mfma_loop_probe(int32_t blocks, int32_t iters, int32_t random_operands, float* sink,
@@ -332,6 +375,6 @@ const char* aeris_winattn_strerror(int code) {
   return "unknown error code";
 }
 
-int aeris_winattn_version(void) { return 110; }
+int aeris_winattn_version(void) { return 120; }
 
 }  // extern "C"

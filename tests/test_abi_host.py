@@ -100,6 +100,18 @@ def test_rope_arguments_rejected_before_launch():
                                       tensor - 1, None) == -8
     assert lib.aeris_winattn_rope_bwd(ctypes.byref(p), ctypes.byref(r), a, a, a, a, a, a, a, a, a,
                                       a, 2 * tensor, None) == -8
+    # the same calls on a list of windows
+    P, R = ctypes.byref(p), ctypes.byref(r)
+    assert lib.aeris_winattn_rope_fwd_windows(P, R, None, 4, a, a, a, a, a, a, tensor, None) == -1
+    assert lib.aeris_winattn_rope_fwd_windows(P, R, a, 0, a, a, a, a, a, a, tensor, None) == -2
+    assert lib.aeris_winattn_rope_fwd_windows(P, R, a, 8 * 16 + 1, a, a, a, a, a, a, tensor, None) == -2
+    assert lib.aeris_winattn_rope_fwd_windows(P, R, a + 2, 4, a, a, a, a, a, a, tensor, None) == -7
+    assert lib.aeris_winattn_rope_fwd_windows(P, R, a, 4, a, a, a, a, a, a, tensor - 1, None) == -8
+    assert lib.aeris_winattn_rope_fwd_windows(P, None, a, 4, a, a, a, a, a, a, tensor, None) == -1
+    assert lib.aeris_winattn_rope_bwd_windows(P, R, a, 4, a, a, a, a, a, a, a, a, a, a, 2 * tensor,
+                                              None) == -8
+    assert lib.aeris_winattn_rope_bwd_windows(P, R, a, 4, a, a, a, a, a, a, a, None, a, a, 1 << 40,
+                                              None) == -1
 
 
 def test_window_list_arguments_rejected_before_launch():

@@ -74,3 +74,39 @@ def test_full_list_equals_plain_call_bitwise():
     assert torch.equal(o1, o2) and torch.equal(l1, l2)
     for a, b in zip(g1, g2):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("mode", [B.AERIS_ROPE_POS_WINDOW, B.AERIS_ROPE_POS_GRID])
+def test_rotary_attention_on_a_window_subset(mode):
+    """A rank's share with the rotary embedding: inside the listed windows the result is bit for
+    bit that of the full-grid rotary calls (which tests/test_gpu_rope.py holds to the oracle);
+    nothing outside them is written, and q, k outside them are never read (NaN there)."""
+    shape, win, shift, mask = (2, 36, 72, 2, 64), (12, 12), (6, 6), B.AERIS_MASK_SWIN
+    Bn, H, W, nh, d = shape
+    picks = [17, 0, 5, 11, 6]          # corner, seam and interior windows of the 3 x 6 grid
+    bits = synth.make_inputs("normal", 6003, shape, 4)
+    tq, tk, tv, tdo = [to_dev(b) for b in bits]
+    o_ref, lse_ref = B.aeris_winattn_rope_fwd(tq, tk, tv, win, shift, 100.0, mode, mask)
+    g_ref = B.aeris_winattn_rope_bwd(tq, tk, tv, o_ref, lse_ref, tdo, win, shift, 100.0, mode, mask)
+    inside = torch.from_numpy(window_token_mask(H, W, win, shift, picks)).cuda()
+    assert 0 < int(inside.sum()) < H * W
+    # poison everything outside the share
+    def share(t):
+        out = torch.full_like(t, float("nan"))
+        out[:, inside] = t[:, inside]
+        return out
+    sq, sk, sv, sdo = share(tq), share(tk), share(tv), share(tdo)
+    lst = torch.tensor(picks, dtype=torch.int32, device="cuda")
+    o = torch.full_like(o_ref, float("nan"))
+    lse = torch.full_like(lse_ref, float("nan"))
+    B.aeris_winattn_rope_fwd_windows(sq, sk, sv, win, shift, 100.0, mode, lst, o, lse, mask)
+    grads = [torch.full_like(tq, float("nan")) for _ in range(3)]
+    B.aeris_winattn_rope_bwd_windows(sq, sk, sv, o, lse, sdo, win, shift, 100.0, mode, lst, *grads,
+                                     mask=mask)
+    torch.cuda.synchronize()
+    assert torch.equal(o[:, inside], o_ref[:, inside])
+    assert torch.equal(lse[:, :, inside], lse_ref[:, :, inside])
+    assert torch.isnan(o[:, ~inside]).all() and torch.isnan(lse[:, :, ~inside]).all()
+    for g, ref in zip(grads, g_ref):
+        assert torch.equal(g[:, inside], ref[:, inside])
+        assert torch.isnan(g[:, ~inside]).all()
