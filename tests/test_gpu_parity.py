@@ -399,3 +399,39 @@ def test_very_peaked_rows_exercise_the_running_maximum(d):
     torch.cuda.synchronize()
     check("o", o, o_ref, False)
     assert (np.abs(to_f64(lse) - lse_ref) <= LSE_ABS + 1e-5 * np.abs(lse_ref)).all()
+
+
+@pytest.mark.parametrize("order", ["rising", "falling", "all_low", "late_spike"])
+def test_forward_reference_point_under_monotone_and_extreme_logits(order):
+    """Logits laid out along the key order so that the forward kernel's reference point has to
+    follow them: rising by more than 2^12 per 32-key block (every block overflows the sum test and
+    rescales), falling (later blocks underflow against an early maximum), all far below zero
+    (nothing may underflow: the first block has to set the reference), and flat with one huge
+    logit in the last block.  One window of 512 tokens, d = 32."""
+    H, W, d = 8, 64, 32
+    T = H * W
+    rng = np.random.default_rng(7)
+    q = np.zeros((1, H, W, 1, d), dtype=np.float32)
+    k = np.zeros_like(q)
+    q[..., 0] = 4.0
+    j = np.arange(T, dtype=np.float32).reshape(H, W)
+    if order == "rising":
+        k[0, :, :, 0, 0] = j * 0.5 - 100.0          # logits from -400 to +622 (natural units)
+    elif order == "falling":
+        k[0, :, :, 0, 0] = 100.0 - j * 0.5
+    elif order == "all_low":
+        k[0, :, :, 0, 0] = -200.0 + 0.01 * rng.standard_normal((H, W)).astype(np.float32)
+    else:
+        k[0, :, :, 0, 0] = 0.01 * rng.standard_normal((H, W)).astype(np.float32)
+        k[0, H - 1, W - 3, 0, 0] = 150.0
+    v = rng.standard_normal(q.shape).astype(np.float32)
+    bits = [synth.f32_to_bf16_bits(a) for a in (q, k, v)]
+    q64, k64, v64 = [synth.bf16_bits_to_f64(b) for b in bits]
+    tq, tk, tv = [to_dev(b) for b in bits]
+    o_ref, lse_ref = orc.winattn_fwd(q64, k64, v64, (H, W), (0, 0), B.AERIS_MASK_NONE, 1.0)
+    assert np.isfinite(lse_ref).all() and np.abs(lse_ref).max() > 300.0
+    o, lse = B.aeris_winattn_fwd(tq, tk, tv, (H, W), (0, 0), B.AERIS_MASK_NONE, 1.0,
+                                 out_dtype=B.AERIS_DT_F32)
+    torch.cuda.synchronize()
+    check("o", o, o_ref, False)
+    assert (np.abs(to_f64(lse) - lse_ref) <= LSE_ABS + 1e-5 * np.abs(lse_ref)).all()
