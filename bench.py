@@ -50,6 +50,11 @@ WORKLOADS = {
 # HBM traffic per launch, bytes, from two rocprofv3 --pmc runs of this file (FETCH_SIZE, then
 # WRITE_SIZE, each scaled by what the same counter reads for the --calibrate-copy kernels:
 # factors 2.000 and 1.000); profiles/c5_kernels_and_counters.txt has the commands and numbers.
+# rocprofv3 FETCH_SIZE + WRITE_SIZE of one launch at 4 x 1,036,800 rows x 2048 channels
+# (profiles/layer_ops_kernel_trace.txt)
+LAYER_OPS_TRAFFIC = {"rmsnorm_adaln_fwd": 34.09e9, "rmsnorm_adaln_bwd": 51.04e9,
+                     "gate_residual_fwd": 50.97e9, "gate_residual_bwd": 50.98e9,
+                     "swiglu_fwd": 25.48e9, "swiglu_bwd": 42.47e9}
 MEASURED_TRAFFIC = {("c5", "fwd"): 74.6e9, ("c5", "dq"): 110.3e9, ("c5", "dkdv"): 113.6e9}
 
 
@@ -324,7 +329,7 @@ def bench_layer_ops(args):
                                      "hidden %d" % (nb, rps, C, C // 2), "kernels": per_kernel},
               "roofline": {"bound": "hbm", "kernel": slow[0], "achieved": round(achieved, 1),
                            "peak": 8000.0, "unit": "GB/s", "frac": round(achieved / 8000.0, 4),
-                           "traffic": None}}
+                           "traffic": LAYER_OPS_TRAFFIC.get(slow[0]) if C == 2048 else None}}
     if not args.no_cpu_baseline:
         from oracle import block_oracle as bo
         rows = 4096
