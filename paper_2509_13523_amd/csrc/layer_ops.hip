@@ -3,7 +3,8 @@
 // gamma, SwiGLU); formulas and argument contracts in include/aeris_layer_ops.h.
 //
 // All of them are bound by HBM traffic: every activation is read once and every result written
-// once, 16 bytes per lane and access, with fp32 arithmetic in between.  Row operations give a
+// once, 16 bytes per lane and access (non-temporal: nothing is reused), with fp32 arithmetic in
+// between.  Row operations give a
 // wavefront one token row at a time (lane l holds the 8-channel vectors l, l + 64, ...), so the
 // row statistics need one cross-lane reduction and no barrier.  A workgroup works on a
 // contiguous chunk of the rows of ONE sample, so the sample's modulation vectors are loaded
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_adaln_fwd_kernel(
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       const int v = k * 64 + lane;
-      raw[k] = (v * 8 < C) ? src[v] : u32x4{0, 0, 0, 0};
+      raw[k] = (v * 8 < C) ? __builtin_nontemporal_load(&src[v]) : u32x4{0, 0, 0, 0};
     }
     float ss = 0.f;
 #pragma unroll
@@ -128,7 +129,7 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_adaln_fwd_kernel(
           o[i] = __builtin_fmaf(f[i] * r, s0[i], b0[i]);
           o[4 + i] = __builtin_fmaf(f[4 + i] * r, s1[i], b1[i]);
         }
-        dst[v] = pack8(o);
+        __builtin_nontemporal_store(pack8(o), &dst[v]);
       }
     }
   }
@@ -199,8 +200,8 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_adaln_bwd_kernel(
     for (int k = 0; k < K; ++k) {
       const int v = k * 64 + lane;
       const bool in = v * 8 < C;
-      xr[k] = in ? xs[v] : u32x4{0, 0, 0, 0};
-      gr[k] = in ? gs[v] : u32x4{0, 0, 0, 0};
+      xr[k] = in ? __builtin_nontemporal_load(&xs[v]) : u32x4{0, 0, 0, 0};
+      gr[k] = in ? __builtin_nontemporal_load(&gs[v]) : u32x4{0, 0, 0, 0};
     }
     const float r = rstd[row];
     float dot = 0.f;
@@ -242,7 +243,7 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_adaln_bwd_kernel(
           const float dn = gf[i] * (i < 4 ? s0[i & 3] : s1[i & 3]);
           o[i] = r * __builtin_fmaf(-n, m, dn);
         }
-        dst[v] = pack8(o);
+        __builtin_nontemporal_store(pack8(o), &dst[v]);
       }
     }
   }
@@ -317,8 +318,8 @@ __global__ __launch_bounds__(kRowThreads) void gate_residual_fwd_kernel(
     for (int k = 0; k < K; ++k) {
       const int v = k * 64 + lane;
       if (v * 8 < C) {
-        xr[k] = xs[v];
-        yr[k] = ys[v];
+        xr[k] = __builtin_nontemporal_load(&xs[v]);
+        yr[k] = __builtin_nontemporal_load(&ys[v]);
       }
     }
 #pragma unroll
@@ -330,7 +331,7 @@ __global__ __launch_bounds__(kRowThreads) void gate_residual_fwd_kernel(
         unpack8(yr[k], yf);
 #pragma unroll
         for (int i = 0; i < 8; ++i) o[i] = __builtin_fmaf(a[k][i], yf[i], xf[i]);
-        dst[v] = pack8(o);
+        __builtin_nontemporal_store(pack8(o), &dst[v]);
       }
     }
   }
@@ -365,8 +366,8 @@ __global__ __launch_bounds__(kRowThreads) void gate_residual_bwd_kernel(
     for (int k = 0; k < K; ++k) {
       const int v = k * 64 + lane;
       const bool in = v * 8 < C;
-      yr[k] = in ? ys[v] : u32x4{0, 0, 0, 0};
-      gr[k] = in ? gs[v] : u32x4{0, 0, 0, 0};
+      yr[k] = in ? __builtin_nontemporal_load(&ys[v]) : u32x4{0, 0, 0, 0};
+      gr[k] = in ? __builtin_nontemporal_load(&gs[v]) : u32x4{0, 0, 0, 0};
     }
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -379,7 +380,7 @@ __global__ __launch_bounds__(kRowThreads) void gate_residual_bwd_kernel(
         o[i] = a[k][i] * gf[i];
         acc[0][k][i] = __builtin_fmaf(gf[i], yf[i], acc[0][k][i]);
       }
-      if (v * 8 < C) dst[v] = pack8(o);
+      if (v * 8 < C) __builtin_nontemporal_store(pack8(o), &dst[v]);
     }
   }
   write_partials<1, K>(acc, lds_f, C, partial);
@@ -404,11 +405,11 @@ __global__ __launch_bounds__(256) void swiglu_fwd_kernel(const bf16_t* __restric
     u32x4* dst = reinterpret_cast<u32x4*>(g + row * F);
     for (int j = threadIdx.x; j < fv; j += 256) {
       float u[8], v[8], o[8];
-      unpack8(us[j], u);
-      unpack8(vs[j], v);
+      unpack8(__builtin_nontemporal_load(&us[j]), u);
+      unpack8(__builtin_nontemporal_load(&vs[j]), v);
 #pragma unroll
       for (int i = 0; i < 8; ++i) o[i] = u[i] * logistic(u[i]) * v[i];
-      dst[j] = pack8(o);
+      __builtin_nontemporal_store(pack8(o), &dst[j]);
     }
   }
 }
@@ -426,17 +427,17 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const bf16_t* uv,
     u32x4* dv = du + fv;
     for (int j = threadIdx.x; j < fv; j += 256) {
       float u[8], v[8], d[8], ou[8], ov[8];
-      unpack8(us[j], u);
-      unpack8(vs[j], v);
-      unpack8(gs[j], d);
+      unpack8(__builtin_nontemporal_load(&us[j]), u);
+      unpack8(__builtin_nontemporal_load(&vs[j]), v);
+      unpack8(__builtin_nontemporal_load(&gs[j]), d);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const float s = logistic(u[i]);
         ou[i] = d[i] * v[i] * s * __builtin_fmaf(u[i], 1.f - s, 1.f);
         ov[i] = d[i] * u[i] * s;
       }
-      du[j] = pack8(ou);
-      dv[j] = pack8(ov);
+      __builtin_nontemporal_store(pack8(ou), &du[j]);
+      __builtin_nontemporal_store(pack8(ov), &dv[j]);
     }
   }
 }
