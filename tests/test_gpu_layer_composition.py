@@ -131,3 +131,62 @@ def test_attention_half_of_a_layer_forward_and_backward():
                                 ("dbeta", f64(tdbeta), dbeta, 8e-3)):
         assert np.isfinite(got).all(), name
         assert rel_l2(got, ref) <= tol, "%s rel_l2 %.3e" % (name, rel_l2(got, ref))
+
+
+def test_swiglu_half_of_a_layer_forward_and_backward():
+    """out = x + alpha * (swiglu(h Wup^T) Wdown^T),  h = RMSNorm(x; w) (1 + gamma) + beta."""
+    Bn, rps, C, F = 3, 500, 256, 512
+    N = Bn * rps
+    eps = 1e-6
+    rng = np.random.default_rng(2025)
+    x = rb(rng.standard_normal((N, C)))
+    dout = rb(rng.standard_normal((N, C)))
+    wup = rb(rng.standard_normal((2 * F, C)) / np.sqrt(C))
+    wdown = rb(rng.standard_normal((C, F)) / np.sqrt(F))
+    w = (1.0 + 0.1 * rng.standard_normal(C)).astype(np.float32).astype(np.float64)
+    gamma = (0.2 * rng.standard_normal((Bn, C))).astype(np.float32).astype(np.float64)
+    beta = (0.3 * rng.standard_normal((Bn, C))).astype(np.float32).astype(np.float64)
+    alpha = (0.8 * rng.standard_normal((Bn, C))).astype(np.float32).astype(np.float64)
+
+    h, _ = bo.rmsnorm_adaln_fwd(x, w, gamma, beta, eps, rps)
+    h = rb(h)
+    uv = rb(h @ wup.T)
+    g = rb(bo.swiglu_fwd(uv))
+    y = rb(g @ wdown.T)
+    out = bo.gate_residual_fwd(x, y, alpha, rps)
+    _, dy, dalpha = bo.gate_residual_bwd(y, alpha, dout, rps)
+    dy = rb(dy)
+    dwdown = dy.T @ g
+    dg = rb(dy @ wdown)
+    duv = rb(bo.swiglu_bwd(uv, dg))
+    dwup = duv.T @ h
+    dh = rb(duv @ wup)
+    dx_norm, dw, dgamma, dbeta = bo.rmsnorm_adaln_bwd(x, w, gamma, beta, eps, rps, dh)
+    dx = dout + dx_norm
+
+    tx, tdout, twup, twdown = dev_bf16(x), dev_bf16(dout), dev_bf16(wup), dev_bf16(wdown)
+    f32 = lambda a_: torch.from_numpy(a_.astype(np.float32)).cuda()
+    tw, tgamma, tbeta, talpha = f32(w), f32(gamma), f32(beta), f32(alpha)
+    th, tr = B.aeris_rmsnorm_adaln_fwd(tx, tw, tgamma, tbeta, eps, rps)
+    tuv = torch.matmul(th, twup.t())
+    tg = B.aeris_swiglu_fwd(tuv)
+    ty = torch.matmul(tg, twdown.t())
+    tout = B.aeris_gate_residual_fwd(tx, ty, talpha, rps)
+    tdy, tdalpha = B.aeris_gate_residual_bwd(ty, talpha, tdout, rps)
+    tdwdown = torch.matmul(tdy.t().float(), tg.float())
+    tdg = torch.matmul(tdy, twdown)
+    tduv = B.aeris_swiglu_bwd(tuv, tdg)
+    tdwup = torch.matmul(tduv.t().float(), th.float())
+    tdh = torch.matmul(tduv, twup)
+    tdxn, tdw, tdgamma, tdbeta = B.aeris_rmsnorm_adaln_bwd(tx, tw, tgamma, tr, tdh, rps)
+    tdx = tdout.float() + tdxn.float()
+    torch.cuda.synchronize()
+
+    # every hand-over is one bf16 rounding on both sides; a value next to a rounding boundary may
+    # round differently on the two sides and is then carried through the rest of the chain
+    for name, got, ref in (("h", f64(th), h), ("uv", f64(tuv), uv), ("g", f64(tg), g), ("out", f64(tout), out),
+                           ("duv", f64(tduv), duv), ("dx", f64(tdx), dx), ("dalpha", f64(tdalpha), dalpha),
+                           ("dwdown", f64(tdwdown), dwdown), ("dwup", f64(tdwup), dwup),
+                           ("dw", f64(tdw), dw), ("dgamma", f64(tdgamma), dgamma), ("dbeta", f64(tdbeta), dbeta)):
+        assert np.isfinite(got).all(), name
+        assert rel_l2(got, ref) <= 2e-3, "%s rel_l2 %.3e" % (name, rel_l2(got, ref))
