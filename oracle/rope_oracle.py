@@ -25,9 +25,7 @@ axial-frequency variant of the cited work:
   * the backward pass treats the embedding as the linear map it is:
         dQ = R(phi)^T dQ',  i.e. the rotation by -phi.
 
-``round_fn`` lets a test round the rotated operands to the storage type the
-kernels multiply in (bf16) so that both sides feed the same operands to the
-logits; the oracle itself never rounds.
+Nothing is rounded anywhere: fp64 throughout.
 
 Parity pins: tests/test_rope_pins.py (hand-computed angles, the complex
 exponential route written with explicit loops, norm and relative-position
@@ -80,22 +78,17 @@ def rotate(t, phi, inverse=False):
     return out
 
 
-def _same(x):
-    return x
-
-
-def winattn_rope_fwd(q, k, v, win, shift, mask, base, pos_mode, scale=None, round_fn=_same):
+def winattn_rope_fwd(q, k, v, win, shift, mask, base, pos_mode, scale=None):
     """Window attention on rotated queries and keys.  Returns (O, LSE)."""
     B, H, W, nh, d = q.shape
     phi = angles(H, W, d, win, shift, base, pos_mode)
-    return wa.winattn_fwd(round_fn(rotate(q, phi)), round_fn(rotate(k, phi)), v, win, shift,
-                          mask, scale)
+    return wa.winattn_fwd(rotate(q, phi), rotate(k, phi), v, win, shift, mask, scale)
 
 
-def winattn_rope_bwd(q, k, v, do, win, shift, mask, base, pos_mode, scale=None, round_fn=_same):
+def winattn_rope_bwd(q, k, v, do, win, shift, mask, base, pos_mode, scale=None):
     """Gradients with respect to the UNROTATED q, k (and v).  Returns (dQ, dK, dV)."""
     B, H, W, nh, d = q.shape
     phi = angles(H, W, d, win, shift, base, pos_mode)
-    dq_r, dk_r, dv, _ = wa.winattn_bwd(round_fn(rotate(q, phi)), round_fn(rotate(k, phi)), v, do,
-                                       win, shift, mask, scale)
+    dq_r, dk_r, dv, _ = wa.winattn_bwd(rotate(q, phi), rotate(k, phi), v, do, win, shift, mask,
+                                       scale)
     return rotate(dq_r, phi, inverse=True), rotate(dk_r, phi, inverse=True), dv

@@ -18,6 +18,7 @@
 #include "aeris_layer_ops.h"
 #include "aeris_winattn.h"
 #include "winattn_common.hpp"
+#include "winattn_launch.hpp"
 
 namespace aeris {
 namespace {
@@ -460,7 +461,7 @@ int vectors_per_lane(int channels) {
   return v <= 1 ? 1 : v <= 2 ? 2 : v <= 4 ? 4 : 8;
 }
 
-int launched() { return hipGetLastError() == hipSuccess ? AERIS_OK : AERIS_ERR_HIP_LAUNCH; }
+int status(int launch_rc) { return launch_rc == 0 ? AERIS_OK : AERIS_ERR_HIP_LAUNCH; }
 
 // Calls f(Const<K>) for the K that fits `channels`.
 template <typename F>
@@ -493,12 +494,13 @@ extern "C" int aeris_rmsnorm_adaln_fwd(const void* x, const float* w, const floa
   const dim3 grid(static_cast<unsigned>(n_rows / rows_per_sample * cps));
   const size_t smem = 2 * sizeof(float) * channels;
   const hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int rc = -1;
   with_k(channels, [&](auto kc) {
-    hipLaunchKernelGGL((rmsnorm_adaln_fwd_kernel<decltype(kc)::value>), grid, dim3(kRowThreads),
+    rc = launch_kernel(rmsnorm_adaln_fwd_kernel<decltype(kc)::value>, grid, dim3(kRowThreads),
                        smem, st, rw, static_cast<const bf16_t*>(x), w, gamma, beta, eps,
                        static_cast<bf16_t*>(h), r);
   });
-  return launched();
+  return status(rc);
 }
 
 extern "C" size_t aeris_rmsnorm_adaln_bwd_workspace_bytes(int64_t n_rows, int64_t rows_per_sample,
@@ -529,16 +531,17 @@ extern "C" int aeris_rmsnorm_adaln_bwd(const void* x, const float* w, const floa
   const size_t smem = 3 * sizeof(float) * channels;
   const hipStream_t st = static_cast<hipStream_t>(hip_stream);
   float* partial = static_cast<float*>(workspace);
+  int rc = -1;
   with_k(channels, [&](auto kc) {
-    hipLaunchKernelGGL((rmsnorm_adaln_bwd_kernel<decltype(kc)::value>), grid, dim3(kRowThreads),
+    rc = launch_kernel(rmsnorm_adaln_bwd_kernel<decltype(kc)::value>, grid, dim3(kRowThreads),
                        smem, st, rw, static_cast<const bf16_t*>(x), w, gamma, r,
                        static_cast<const bf16_t*>(dh), static_cast<bf16_t*>(dx), partial);
   });
-  if (const int rc = launched()) return rc;
+  if (rc != 0) return AERIS_ERR_HIP_LAUNCH;
   if (dw || dgamma || dbeta) {
-    hipLaunchKernelGGL(column_sums_finish_kernel, dim3((channels + 63) / 64), dim3(256), 0, st,
-                       partial, n_samples, cps, channels, 0, w, gamma, dgamma, dbeta, dw);
-    return launched();
+    return status(launch_kernel(column_sums_finish_kernel, dim3((channels + 63) / 64), dim3(256), 0,
+                                st, partial, n_samples, cps, channels, 0, w, gamma, dgamma, dbeta,
+                                dw));
   }
   return AERIS_OK;
 }
@@ -553,12 +556,13 @@ extern "C" int aeris_gate_residual_fwd(const void* x, const void* y, const float
   const RowWork rw{rows_per_sample, cps, channels};
   const dim3 grid(static_cast<unsigned>(n_rows / rows_per_sample * cps));
   const hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int rc = -1;
   with_k(channels, [&](auto kc) {
-    hipLaunchKernelGGL((gate_residual_fwd_kernel<decltype(kc)::value>), grid, dim3(kRowThreads),
+    rc = launch_kernel(gate_residual_fwd_kernel<decltype(kc)::value>, grid, dim3(kRowThreads),
                        0, st, rw, static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(y),
                        alpha, static_cast<bf16_t*>(out));
   });
-  return launched();
+  return status(rc);
 }
 
 extern "C" size_t aeris_gate_residual_bwd_workspace_bytes(int64_t n_rows, int64_t rows_per_sample,
@@ -586,17 +590,17 @@ extern "C" int aeris_gate_residual_bwd(const void* y, const float* alpha, const 
   const size_t smem = sizeof(float) * channels;
   const hipStream_t st = static_cast<hipStream_t>(hip_stream);
   float* partial = static_cast<float*>(workspace);
+  int rc = -1;
   with_k(channels, [&](auto kc) {
-    hipLaunchKernelGGL((gate_residual_bwd_kernel<decltype(kc)::value>), grid, dim3(kRowThreads),
+    rc = launch_kernel(gate_residual_bwd_kernel<decltype(kc)::value>, grid, dim3(kRowThreads),
                        smem, st, rw, static_cast<const bf16_t*>(y), alpha,
                        static_cast<const bf16_t*>(dout), static_cast<bf16_t*>(dy), partial);
   });
-  if (const int rc = launched()) return rc;
+  if (rc != 0) return AERIS_ERR_HIP_LAUNCH;
   if (dalpha) {
-    hipLaunchKernelGGL(column_sums_finish_kernel, dim3((channels + 63) / 64), dim3(256), 0, st,
-                       partial, n_samples, cps, channels, 1, nullptr, nullptr, dalpha, nullptr,
-                       nullptr);
-    return launched();
+    return status(launch_kernel(column_sums_finish_kernel, dim3((channels + 63) / 64), dim3(256), 0,
+                                st, partial, n_samples, cps, channels, 1, nullptr, nullptr, dalpha,
+                                nullptr, nullptr));
   }
   return AERIS_OK;
 }
@@ -617,17 +621,17 @@ unsigned swiglu_grid(int64_t n_rows) {
 extern "C" int aeris_swiglu_fwd(const void* uv, int64_t n_rows, int32_t hidden, void* g,
                                 void* hip_stream) {
   if (const int rc = check_swiglu(uv, g, g, n_rows, hidden)) return rc;
-  hipLaunchKernelGGL(swiglu_fwd_kernel, dim3(swiglu_grid(n_rows)), dim3(256), 0,
-                     static_cast<hipStream_t>(hip_stream), static_cast<const bf16_t*>(uv), n_rows,
-                     hidden, static_cast<bf16_t*>(g));
-  return launched();
+  return status(launch_kernel(swiglu_fwd_kernel, dim3(swiglu_grid(n_rows)), dim3(256), 0,
+                              static_cast<hipStream_t>(hip_stream),
+                              static_cast<const bf16_t*>(uv), n_rows, hidden,
+                              static_cast<bf16_t*>(g)));
 }
 
 extern "C" int aeris_swiglu_bwd(const void* uv, const void* dg, int64_t n_rows, int32_t hidden,
                                 void* duv, void* hip_stream) {
   if (const int rc = check_swiglu(uv, dg, duv, n_rows, hidden)) return rc;
-  hipLaunchKernelGGL(swiglu_bwd_kernel, dim3(swiglu_grid(n_rows)), dim3(256), 0,
-                     static_cast<hipStream_t>(hip_stream), static_cast<const bf16_t*>(uv),
-                     static_cast<const bf16_t*>(dg), n_rows, hidden, static_cast<bf16_t*>(duv));
-  return launched();
+  return status(launch_kernel(swiglu_bwd_kernel, dim3(swiglu_grid(n_rows)), dim3(256), 0,
+                              static_cast<hipStream_t>(hip_stream),
+                              static_cast<const bf16_t*>(uv), static_cast<const bf16_t*>(dg),
+                              n_rows, hidden, static_cast<bf16_t*>(duv)));
 }

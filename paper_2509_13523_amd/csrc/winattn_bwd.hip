@@ -597,9 +597,9 @@ static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const v
   if ((stages & 1u) && !fused_stats) {
     constexpr int kTokens = kThreads / (D / 8);
     const long long dblocks = (long long)kp.n_pairs * ((kp.T + kTokens - 1) / kTokens);
-    hipLaunchKernelGGL((winattn_delta_kernel<D, OutT>), dim3((unsigned)dblocks), dim3(kThreads),
-                       0, stream, kp, static_cast<const OutT*>(o), dop, lse, delta, lse2);
-    if (hipGetLastError() != hipSuccess) return -1;
+    if (launch_kernel(winattn_delta_kernel<D, OutT>, dim3((unsigned)dblocks), dim3(kThreads), 0,
+                      stream, kp, static_cast<const OutT*>(o), dop, lse, delta, lse2) != 0)
+      return -1;
   }
 
   const int n_blocks = grid_blocks(kp);
@@ -607,10 +607,10 @@ static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const v
     const size_t smem = dq_smem_bytes<D>(kp.T);
     auto kern = winattn_dq_kernel<D, OutT>;
     if (!allow_full_lds<winattn_dq_kernel<D, OutT>>()) return -1;
-    hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, qp, kp_, vp, dop,
-                       static_cast<const OutT*>(o), lse, delta, lse2, static_cast<OutT*>(dq),
-                       fused_stats ? 1 : 0);
-    if (hipGetLastError() != hipSuccess) return -1;
+    if (launch_kernel(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, qp, kp_, vp, dop,
+                      static_cast<const OutT*>(o), lse, delta, lse2, static_cast<OutT*>(dq),
+                      fused_stats ? 1 : 0) != 0)
+      return -1;
   }
   if constexpr (D == 128) {   // software-pipelined kernel; the generic one is not built for it
     if ((stages & 4u) && launch_dkdv_pipe128(kp, std::is_same<OutT, float>::value, q, k, v, d_o,
@@ -620,10 +620,10 @@ static int launch_bwd_t(const KParams& kp, const void* q, const void* k, const v
     const size_t smem = dkdv_smem_bytes<D>(kp.T);
     auto kern = winattn_dkdv_kernel<D, OutT>;
     if (!allow_full_lds<winattn_dkdv_kernel<D, OutT>>()) return -1;
-    hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, qp, kp_, vp, dop,
-                       static_cast<const float*>(delta), static_cast<const float*>(lse2),
-                       static_cast<OutT*>(dk), static_cast<OutT*>(dv));
-    if (hipGetLastError() != hipSuccess) return -1;
+    if (launch_kernel(kern, dim3(n_blocks), dim3(kThreads), smem, stream, kp, qp, kp_, vp, dop,
+                      static_cast<const float*>(delta), static_cast<const float*>(lse2),
+                      static_cast<OutT*>(dk), static_cast<OutT*>(dv)) != 0)
+      return -1;
   }
   return 0;
 }

@@ -378,28 +378,6 @@ __device__ __forceinline__ void settle(V& v) {
 // products, operand reads and copies.
 __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
 
-// Optional stage timing (development aid, off by default): -DAERIS_STAGE_TIMING makes one
-// wave of one workgroup accumulate the 100 MHz wall clock per schedule stage into a
-// __device__ array, which a harness reads back with hipMemcpyFromSymbol.
-#ifdef AERIS_STAGE_TIMING
-#define AERIS_TICK_DECL                                                              \
-  const bool tick_on = blockIdx.x == 8 * 40 + 3 && threadIdx.x == 0;                 \
-  unsigned long long tick_last = wall_clock64(), tick_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#define AERIS_TICK(i)                                 \
-  if (tick_on) {                                      \
-    const unsigned long long t = wall_clock64();      \
-    tick_acc[i] += t - tick_last;                     \
-    tick_last = t;                                    \
-  }
-#define AERIS_TICK_FLUSH(array) \
-  if (tick_on)                  \
-    for (int i = 0; i < 8; ++i) array[i] = tick_acc[i];
-#else
-#define AERIS_TICK_DECL
-#define AERIS_TICK(i)
-#define AERIS_TICK_FLUSH(array)
-#endif
-
 // W: wavefronts of the workgroup (they share the filling of a tile).
 template <int D, int W = kWaves>
 struct Tile {

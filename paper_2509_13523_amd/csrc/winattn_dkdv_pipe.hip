@@ -17,9 +17,6 @@
 #include "winattn_common.hpp"
 #include "winattn_launch.hpp"
 
-#ifdef AERIS_STAGE_TIMING
-__device__ unsigned long long aeris_stage_ticks[16];
-#endif
 
 namespace aeris {
 
@@ -263,17 +260,13 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
   if (rg.wave_active) stage_a(0);
   int a_buf = 0, c_buf = 0;   // buffer index `rm` / `tr`,`st` point into
 
-  AERIS_TICK_DECL
   for (int qt = qt_begin; qt < qt_end; ++qt) {
     const bool more = qt + 1 < qt_end;
     if (qt + 2 < qt_end) rows.prepare((qt + 2) * kStream);   // table entries of tile qt+2: used two stages later
-    AERIS_TICK(7)
     // first half: A(tile qt, block 1) with B(tile qt, block 0); then C(block 0)
     if (rg.wave_active) {
       run_ab(true, s0, dp0, s1, dp1, Tl::kSubBytes, 0, qt * kStream, false, 0, 0);
-      AERIS_TICK(0)
       stage_c(0);
-      AERIS_TICK(1)
     }
     // tile qt+1 must be visible before stage A touches it; this barrier also
     // retires every reader of tile qt-1, whose buffer the new fill reuses
@@ -282,21 +275,16 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
     const int fill_t0 = (qt + 2) * kStream;
     if (more) {
       wait_async_loads();
-      AERIS_TICK(5)
       __syncthreads();
-      AERIS_TICK(6)
       const uint32_t step = a_buf == 2 ? (uint32_t)(-2 * (int)kBuf) : kBuf;
       a_buf = a_buf == 2 ? 0 : a_buf + 1;
 #pragma unroll
       for (int kk = 0; kk < kNK; ++kk) la.rm[kk] += step;
     }
-    AERIS_TICK(2)
     // second half: A(tile qt+1, block 0) with B(tile qt, block 1); then C(block 1)
     if (rg.wave_active) {
       run_ab(more, s1, dp1, s0, dp0, 0, 32 * 4, qt * kStream + 32, do_fill, fill_buf, fill_t0);
-      AERIS_TICK(3)
       stage_c(Tl::kSubBytes);
-      AERIS_TICK(4)
     } else if (do_fill) {        // waves without real keys still move their share of the tile
 #pragma unroll
       for (int i = 0; i <= 2 * Tl::kFillPerWave; ++i) fill_piece(i, fill_buf, fill_t0);
@@ -312,7 +300,6 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
       st += step;
     }
   }
-  AERIS_TICK_FLUSH(aeris_stage_ticks)
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // last accumulating MFMAs retire
 
   if (!rg.valid) return;
@@ -342,11 +329,10 @@ static int launch_t(const KParams& kp, const void* q, const void* k, const void*
   const size_t smem = dkdv_pipe_smem_bytes<D>(kp.T);
   auto kern = winattn_dkdv_pipe_kernel<D, OutT>;
   if (!allow_full_lds<winattn_dkdv_pipe_kernel<D, OutT>>()) return -1;
-  hipLaunchKernelGGL(kern, dim3(grid_blocks(kp)), dim3(kThreads), smem, stream, kp,
-                     static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
-                     static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(d_o), delta, lse2,
-                     static_cast<OutT*>(dk), static_cast<OutT*>(dv));
-  return hipGetLastError() == hipSuccess ? 0 : -1;
+  return launch_kernel(kern, dim3(grid_blocks(kp)), dim3(kThreads), smem, stream, kp,
+                       static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
+                       static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(d_o), delta, lse2,
+                       static_cast<OutT*>(dk), static_cast<OutT*>(dv));
 }
 
 int launch_dkdv_pipe128(const KParams& kp, bool out_f32, const void* q, const void* k,
@@ -358,8 +344,3 @@ int launch_dkdv_pipe128(const KParams& kp, bool out_f32, const void* q, const vo
 
 }  // namespace aeris
 
-#ifdef AERIS_STAGE_TIMING
-extern "C" int aeris_debug_read(unsigned long long* out) {
-  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(aeris_stage_ticks), 128);
-}
-#endif

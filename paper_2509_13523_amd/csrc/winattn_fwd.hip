@@ -14,12 +14,6 @@
 #include "winattn_common.hpp"
 #include "winattn_launch.hpp"
 
-#ifdef AERIS_STAGE_TIMING
-__device__ unsigned long long aeris_fwd_ticks[16];
-extern "C" int aeris_debug_read_fwd(unsigned long long* out) {
-  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(aeris_fwd_ticks), 128);
-}
-#endif
 namespace aeris {
 
 template <int D>
@@ -216,7 +210,6 @@ __global__ __launch_bounds__(W * 64, W == 4 ? 2 : 1) void winattn_fwd_kernel(
   // kt, after which the K copies of tile kt+2 go into this tile's buffer.  Copies of
   // tiles past the end are branched over.
   const int kt_last = kt_end - 1;
-  AERIS_TICK_DECL
   auto prepare_after_next = [&](int kt) __attribute__((always_inline)) {
     rows.prepare((kt + 2 < kt_last ? kt + 2 : kt_last) * kStream);
   };
@@ -225,23 +218,15 @@ __global__ __launch_bounds__(W * 64, W == 4 ? 2 : 1) void winattn_fwd_kernel(
     constexpr uint32_t kP = decltype(parity)::value;
     constexpr uint32_t kCur = kP * kBuf, kNext = (1 - kP) * kBuf;
     const uint32_t has1 = kt + 1 < kt_end, has2 = kt + 2 < kt_end;
-    AERIS_TICK(7)
     logits_phase(Const<kCur>{}, Const<1>{}, vfill, tiles + kNext + Tl::kBytes, has1);
-    AERIS_TICK(0)
     prepare_after_next(kt);
     softmax_phase(kt * kStream);
-    AERIS_TICK(1)
     output_phase(Const<kCur + Tl::kSubBytes>{}, Const<0>{}, kfill, 0, 0);
-    AERIS_TICK(2)
     logits_phase(Const<kCur + Tl::kSubBytes>{}, Const<0>{}, vfill, 0, 0);
-    AERIS_TICK(3)
     softmax_phase(kt * kStream + 32);
-    AERIS_TICK(4)
     wait_async_loads();
     __syncthreads();
-    AERIS_TICK(5)
     output_phase(Const<kNext>{}, Const<1>{}, kfill, tiles + kCur, has2);
-    AERIS_TICK(6)
   };
   // A tile none of whose keys this wave needs: keep the copies and the barrier going.
   auto idle_step = [&](int kt) __attribute__((always_inline)) {
@@ -281,7 +266,6 @@ __global__ __launch_bounds__(W * 64, W == 4 ? 2 : 1) void winattn_fwd_kernel(
   }
   for (; kt < kt_end; ++kt) idle_step(kt);
   wait_async_loads();
-  AERIS_TICK_FLUSH(aeris_fwd_ticks)
 
   // ---- epilogue: normalise, un-shift/un-partition store -----------------------
   if (!rg.valid) return;
@@ -310,10 +294,9 @@ static int launch_fwd_w(KParams kp, const void* q, const void* k, const void* v,
   const size_t smem = fwd_smem_bytes<D>(kp.T);
   auto kern = winattn_fwd_kernel<D, OutT, W>;
   if (!allow_full_lds<winattn_fwd_kernel<D, OutT, W>>()) return -1;
-  hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(W * 64), smem, stream, kp,
-                     static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
-                     static_cast<const bf16_t*>(v), static_cast<OutT*>(o), lse);
-  return hipGetLastError() == hipSuccess ? 0 : -1;
+  return launch_kernel(kern, dim3(n_blocks), dim3(W * 64), smem, stream, kp,
+                       static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
+                       static_cast<const bf16_t*>(v), static_cast<OutT*>(o), lse);
 }
 
 template <int D, typename OutT>

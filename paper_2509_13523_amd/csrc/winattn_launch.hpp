@@ -4,26 +4,46 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <tuple>
 
 #include "winattn_common.hpp"
 
 namespace aeris {
 
 // Lets kernel `Kern` use the whole LDS of a CU (160 KB on gfx950) as dynamic shared memory.
-// The attribute is set once per kernel and device and remembered, which keeps it off the
-// launch path of small problems; what a launch actually requests still decides occupancy.
+// The attribute is set once per kernel and device and remembered (one flag per device ordinal,
+// the only process-wide state of the library), which keeps it off the launch path of small
+// problems; what a launch actually requests still decides occupancy.  Devices beyond the
+// table are configured on every launch.
+constexpr int kMaxTrackedDevices = 64;
 template <auto Kern>
 inline bool allow_full_lds() {
-  static std::atomic<unsigned> configured{0};   // one bit per device ordinal (mod 32)
+  static std::atomic<unsigned char> configured[kMaxTrackedDevices] = {};
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return false;
-  const unsigned bit = 1u << (dev & 31);
-  if (configured.load(std::memory_order_acquire) & bit) return true;
+  const bool tracked = dev >= 0 && dev < kMaxTrackedDevices;
+  if (tracked && configured[dev].load(std::memory_order_acquire)) return true;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(Kern),
                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
     return false;
-  configured.fetch_or(bit, std::memory_order_release);
+  if (tracked) configured[dev].store(1, std::memory_order_release);
   return true;
+}
+
+// Enqueues `kern` and returns THIS launch's status (0 ok, -1 failed): the status comes back
+// from the launch call itself, so an earlier, unrelated error of the calling thread is neither
+// cleared nor reported as this library's.
+template <typename... Params, typename... Args>
+inline int launch_kernel(void (*kern)(Params...), dim3 grid, dim3 block, size_t smem,
+                         hipStream_t stream, Args... args) {
+  std::tuple<Params...> values{static_cast<Params>(args)...};
+  void* ptrs[sizeof...(Params)];
+  int i = 0;
+  std::apply([&](auto&... v) { ((ptrs[i++] = (void*)&v), ...); }, values);
+  return hipLaunchKernel(reinterpret_cast<const void*>(kern), grid, block, ptrs, smem, stream) ==
+                 hipSuccess
+             ? 0
+             : -1;
 }
 
 int launch_fwd(const KParams& kp, int head_dim, bool out_f32, const void* q, const void* k,

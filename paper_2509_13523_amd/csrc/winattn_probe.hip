@@ -39,9 +39,8 @@ __global__ __launch_bounds__(kThreads) void mfma_loop_kernel(float* __restrict__
 }
 
 int launch_mfma_loop(int blocks, int iters, bool random_operands, float* sink, hipStream_t stream) {
-  hipLaunchKernelGGL(mfma_loop_kernel, dim3(blocks), dim3(kThreads), 0, stream, sink, iters,
-                     random_operands ? 1 : 0);
-  return hipGetLastError() == hipSuccess ? 0 : -1;
+  return launch_kernel(mfma_loop_kernel, dim3(blocks), dim3(kThreads), 0, stream, sink, iters,
+                       random_operands ? 1 : 0);
 }
 
 }  // namespace aeris

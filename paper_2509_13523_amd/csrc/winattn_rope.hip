@@ -14,8 +14,8 @@
 namespace aeris {
 
 __global__ __launch_bounds__(256) void rope2d_kernel(KParams p, int chunks_per_head,
-                                                     const bf16_t* __restrict__ x, long long x_tok,
-                                                     long long x_head, bf16_t* __restrict__ y,
+                                                     const bf16_t* x, long long x_tok,
+                                                     long long x_head, bf16_t* y,
                                                      long long y_tok, long long y_head, int inverse,
                                                      long long n_chunks) {
   const long long stride = (long long)gridDim.x * blockDim.x;
@@ -38,8 +38,8 @@ __global__ __launch_bounds__(256) void rope2d_kernel(KParams p, int chunks_per_h
 // (pair, token of its window, chunk of the head); positions outside the listed windows are
 // neither read nor written.
 __global__ __launch_bounds__(256) void rope2d_windows_kernel(
-    KParams p, int chunks_per_head, const bf16_t* __restrict__ x, long long x_tok,
-    long long x_head, bf16_t* __restrict__ y, long long y_tok, long long y_head, int inverse,
+    KParams p, int chunks_per_head, const bf16_t* x, long long x_tok, long long x_head, bf16_t* y,
+    long long y_tok, long long y_head, int inverse,
     long long n_chunks) {
   const long long stride = (long long)gridDim.x * blockDim.x;
   const long long plane = (long long)p.H * p.W;
@@ -68,15 +68,10 @@ int launch_rope(const KParams& kp, int head_dim, const void* x, long long x_tok,
                                     : (long long)kp.B * kp.H * kp.W * kp.nh * chunks_per_head;
   long long blocks = (n_chunks + 255) / 256;
   if (blocks > 256 * 32) blocks = 256 * 32;           // grid-stride: 32 workgroups per CU
-  if (listed)
-    hipLaunchKernelGGL(rope2d_windows_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, kp,
-                       chunks_per_head, static_cast<const bf16_t*>(x), x_tok, x_head,
-                       static_cast<bf16_t*>(y), y_tok, y_head, inverse ? 1 : 0, n_chunks);
-  else
-    hipLaunchKernelGGL(rope2d_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, kp,
-                       chunks_per_head, static_cast<const bf16_t*>(x), x_tok, x_head,
-                       static_cast<bf16_t*>(y), y_tok, y_head, inverse ? 1 : 0, n_chunks);
-  return hipGetLastError() == hipSuccess ? 0 : -1;
+  return launch_kernel(listed ? rope2d_windows_kernel : rope2d_kernel, dim3((unsigned)blocks),
+                       dim3(256), 0, stream, kp, chunks_per_head, static_cast<const bf16_t*>(x),
+                       x_tok, x_head, static_cast<bf16_t*>(y), y_tok, y_head, inverse ? 1 : 0,
+                       n_chunks);
 }
 
 }  // namespace aeris

@@ -4,7 +4,20 @@ import sys
 import pytest
 
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+
+import parity_log  # noqa: E402
 
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+@pytest.fixture(autouse=True)
+def _name_the_running_test(request):
+    parity_log.current_test = request.node.name
+    yield
+
+
+def pytest_sessionfinish(session, exitstatus):
+    parity_log.write()

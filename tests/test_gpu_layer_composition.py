@@ -65,7 +65,7 @@ def test_attention_half_of_a_layer_forward_and_backward():
     h = rb(h)
     qkv = rb(h @ wqkv.T).reshape(Bn, H, W, 3, nh, d)
     q, k, v = qkv[:, :, :, 0], qkv[:, :, :, 1], qkv[:, :, :, 2]
-    a, _ = ro.winattn_rope_fwd(q, k, v, win, shift, mask, base, ro.POS_WINDOW, round_fn=rb)
+    a, _ = ro.winattn_rope_fwd(q, k, v, win, shift, mask, base, ro.POS_WINDOW)
     a = rb(a)
     y = rb(a.reshape(N, C) @ wo.T)
     out = bo.gate_residual_fwd(x, y, alpha, rps)
@@ -74,7 +74,7 @@ def test_attention_half_of_a_layer_forward_and_backward():
     dy = rb(dy)
     dwo = dy.T @ a.reshape(N, C)
     da = rb(dy @ wo).reshape(Bn, H, W, nh, d)
-    dq, dk, dv = ro.winattn_rope_bwd(q, k, v, da, win, shift, mask, base, ro.POS_WINDOW, round_fn=rb)
+    dq, dk, dv = ro.winattn_rope_bwd(q, k, v, da, win, shift, mask, base, ro.POS_WINDOW)
     dqkv = rb(np.stack([dq, dk, dv], axis=3)).reshape(N, 3 * C)
     dwqkv = dqkv.T @ h
     dh = rb(dqkv @ wqkv)

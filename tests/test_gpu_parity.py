@@ -1,12 +1,16 @@
 """GPU parity: the HIP library (through its C ABI) against the fp64 oracle.
 
 Tolerances (bf16 operands, fp32 accumulation): relative L2 <= 5e-3 and
-max-abs <= 2e-2 on O, dQ, dK, dV; |LSE error| <= 1e-2.  The absolute bound is
-meant for unit-scale tensors (N(0,1) operands give outputs with max |x| of about
-4): bf16 carries 8 significant bits, so the rounding of a stored value and of P
-or dS before the second product is relative to the magnitude.  For a reference
-tensor whose largest magnitude exceeds 4 the max-abs bound is scaled up by
-max|ref| / 4; relative L2 is always held to 5e-3.
+max-abs <= 2e-2 on O, dQ, dK, dV; |LSE error| <= 1e-2.
+
+Outputs delivered in fp32 are held to exactly these numbers.  Outputs delivered in
+bf16 carry the rounding of the stored value, which is relative to its magnitude
+(8 significant bits: half an ulp is 2^-9 |x|, i.e. 1.6e-2 at |x| = 8): for them the
+max-abs bound is scaled by max|ref| / 4 once the reference exceeds 4 in magnitude
+(N(0,1) operands give outputs with max |x| of about 4); relative L2 stays 5e-3.
+The fp32-output run is the parity figure; the bf16-output run sits beside it.
+Every comparison is logged (tests/parity_log.py): test, tensor, output type,
+measured rel-L2, max-abs, max|ref| and the bound that was applied.
 """
 import numpy as np
 import pytest
@@ -15,6 +19,7 @@ import torch
 from oracle import winattn_oracle as orc
 from paper_2509_13523_amd import binding as B
 from paper_2509_13523_amd import synth
+import parity_log
 
 pytestmark = pytest.mark.gpu
 
@@ -30,15 +35,28 @@ def to_f64(t):
     return t.float().cpu().numpy().astype(np.float64)
 
 
-def check(name, got, ref, bf16_out):
+def check(name, got, ref, bf16_out, scale_abs=None):
+    """scale_abs: scale the max-abs bound by max|ref| / 4 (default: bf16 outputs only)."""
+    if scale_abs is None:
+        scale_abs = bf16_out
     got = to_f64(got) if isinstance(got, torch.Tensor) else got
     assert np.isfinite(got).all(), name
     # a one-token window has dQ = dK = 0 exactly: allow an absolute floor of 1e-5 per element
     rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 2e-3 * np.sqrt(ref.size))
     err = np.abs(got - ref)
+    max_ref = np.abs(ref).max()
+    tol = MAX_ABS * (max(1.0, max_ref / 4.0) if scale_abs else 1.0)
+    parity_log.add(name, "bf16" if bf16_out else "f32", rel, err.max(), max_ref, tol)
     assert rel <= REL_L2, "%s rel_l2 %.3e" % (name, rel)
-    tol = MAX_ABS * max(1.0, np.abs(ref).max() / 4.0)
     assert err.max() <= tol, "%s max_abs %.3e > %.3e" % (name, err.max(), tol)
+
+
+def check_lse(got, ref, rel=0.0):
+    got = to_f64(got) if isinstance(got, torch.Tensor) else got
+    err = np.abs(got - ref)
+    parity_log.add("lse", "f32", np.linalg.norm(err) / np.linalg.norm(ref), err.max(),
+                   np.abs(ref).max(), LSE_ABS)
+    assert (err <= LSE_ABS + rel * np.abs(ref)).all()
 
 
 def handover_bounds(qw, kw, vw, dow, reg, scale):
@@ -52,12 +70,17 @@ def handover_bounds(qw, kw, vw, dow, reg, scale):
 
 
 def check_with_bound(name, got, ref, bound):
+    """bf16 hand-over of O only: the plain tolerance plus the first-order bound above."""
     err = np.abs(got - ref)
     assert np.isfinite(got).all(), name
     excess = np.maximum(err - bound, 0.0)
-    tol = MAX_ABS * max(1.0, np.abs(ref).max() / 4.0)
+    max_ref = np.abs(ref).max()
+    tol = MAX_ABS * max(1.0, max_ref / 4.0)
+    nref = np.linalg.norm(ref)
+    parity_log.add(name, "bf16", np.linalg.norm(err) / nref, err.max(), max_ref, tol,
+                   np.linalg.norm(bound) / nref)
     assert excess.max() <= tol, "%s max_abs excess %.3e > %.3e" % (name, excess.max(), tol)
-    assert np.linalg.norm(err) <= REL_L2 * np.linalg.norm(ref) + np.linalg.norm(bound), name
+    assert np.linalg.norm(err) <= REL_L2 * nref + np.linalg.norm(bound), name
 
 
 def run_case(shape, win, shift, mask, kind="normal", seed=1, bwd=True, scale=None,
@@ -73,7 +96,7 @@ def run_case(shape, win, shift, mask, kind="normal", seed=1, bwd=True, scale=Non
         o, lse = B.aeris_winattn_fwd(tq, tk, tv, win, shift, mask, scale, out_dtype=out)
         torch.cuda.synchronize()
         check("o", o, o_ref, bf)
-        assert np.abs(to_f64(lse) - lse_ref).max() <= LSE_ABS
+        check_lse(lse, lse_ref)
         if bwd:
             dq, dk, dv = B.aeris_winattn_bwd(tq, tk, tv, o, lse, tdo, win, shift, mask, scale,
                                              out_dtype=out)
@@ -128,7 +151,7 @@ def test_config2_smooth_bf16_handover():
     torch.cuda.synchronize()
     check("o", o, o_ref, True)
     check("dv", dv, dv_ref, True)
-    assert np.abs(to_f64(lse) - lse_ref).max() <= LSE_ABS
+    check_lse(lse, lse_ref)
     check_with_bound("dq", to_f64(dq), dq_ref, bq)
     check_with_bound("dk", to_f64(dk), dk_ref, bk)
 
@@ -189,7 +212,7 @@ def test_windows_between_the_narrow_and_wide_forward_tiles(d):
 
 def test_config5_unshifted_layer_fwd_bwd_sampled():
     # the other layer of the bench step: shift 0 (no seam, no mask effect)
-    samples = [(1, 0, 0, 3), (2, 6, 17, 12)]
+    samples = [(0, 2, 9, 5), (1, 0, 0, 3), (2, 6, 17, 12), (3, 11, 20, 0)]
     sampled_check((4, 720, 1440, 16, 128), (60, 60), (0, 0), B.AERIS_MASK_SWIN, "blend", 5001,
                   True, samples, sigmas=[0.1, 0.5, 1.0, 2.0])
 
@@ -260,48 +283,86 @@ def test_errors_raise_on_gpu_box():
 
 
 # ---- full-size workloads (bench launch configuration): sampled pairs + invariants -------
-def sampled_check(shape, win, shift, mask, kind, seed, bwd, samples, sigmas=None):
+def rows_sum(fn, n_rows, step=48):
+    """sum over latitude rows of fn(row slice), in pieces (full-size grids: no whole-tensor
+    float64 temporaries)."""
+    total = None
+    for r0 in range(0, n_rows, step):
+        part = fn(slice(r0, min(r0 + step, n_rows)))
+        total = part if total is None else total + part
+    return total
+
+
+def sampled_check(shape, win, shift, mask, kind, seed, bwd, samples, sigmas=None,
+                  outs=(B.AERIS_DT_F32, B.AERIS_DT_BF16)):
+    """Full-size launch: whole-grid invariants plus sampled (batch, window, head) pairs against
+    the oracle.  With fp32 outputs everything is held to the plain tolerance; with bf16 outputs
+    O reaches the backward pass rounded, and dQ, dK get the plain tolerance plus the
+    delta-perturbation bound (see test_config2_smooth_bf16_handover).
+
+    One fp32 case needs the magnitude scaling of the max-abs bound as well: the noise-level-2
+    ensemble member of config 5.  Its operands have a standard deviation of about 2.2 (|V| up to
+    10) and its softmax rows are peaked, so O is close to P_max * V_j with P_max rounded to bf16
+    before the product (2^-9 relative): 2^-9 * 10 = 2e-2 by itself.  Measured: max-abs 2.9e-2 at
+    max|O| = 9.9, relative L2 1.2e-3.  Members whose noise level exceeds 1 are therefore checked
+    with the bound scaled by max|ref| / 4 for fp32 outputs too; every other fp32 comparison in
+    this file is held to the plain 2e-2."""
     Bn, H, W, nh, d = shape
+    torch.cuda.empty_cache()
     tensors = synth.make_inputs_device(kind, seed, shape, 4 if bwd else 3, sigmas=sigmas)
     tq, tk, tv = tensors[:3]
-    o, lse = B.aeris_winattn_fwd(tq, tk, tv, win, shift, mask)
-    if bwd:
-        tdo = tensors[3]
-        dq, dk, dv = B.aeris_winattn_bwd(tq, tk, tv, o, lse, tdo, win, shift, mask)
-    torch.cuda.synchronize()
-    assert torch.isfinite(o.view(-1)[:: 997].float()).all()
-    # whole-grid properties that hold at any size
-    vmin = tv.amin(dim=(1, 2)).float()
-    vmax = tv.amax(dim=(1, 2)).float()
-    assert (o.amax(dim=(1, 2)).float() <= vmax + 1e-2).all()
-    assert (o.amin(dim=(1, 2)).float() >= vmin - 1e-2).all()
-    if bwd:
-        for b in range(Bn):
-            s_dv = dv[b].double().sum(dim=(0, 1))
-            s_do = tdo[b].double().sum(dim=(0, 1))
-            scale_ = dv[b].double().abs().sum(dim=(0, 1))
-            assert ((s_dv - s_do).abs() <= 2e-3 * scale_ + 1e-2).all()
-            qa = (tq[b].double() * dq[b].double()).sum(dim=(0, 1, 3))
-            kb = (tk[b].double() * dk[b].double()).sum(dim=(0, 1, 3))
-            mag = (tq[b].double() * dq[b].double()).abs().sum(dim=(0, 1, 3))
-            assert ((qa - kb).abs() <= 5e-3 * mag + 1e-2).all()
+    tdo = tensors[3] if bwd else None
+    refs = []
     for (b, wy, wx, h) in samples:
         sl = lambda t: to_f64(t[b, :, :, h, :])
-        res = orc.winattn_pair(sl(tq), sl(tk), sl(tv), sl(tdo) if bwd else None, H, W, win,
-                               shift, mask, None, wy, wx)
-        y, x = res["y"], res["x"]
-        check("o", to_f64(o[b, :, :, h, :])[y, x], res["o"], True)
-        assert np.abs(to_f64(lse[b, h])[y, x] - res["lse"]).max() <= LSE_ABS
+        refs.append(orc.winattn_pair(sl(tq), sl(tk), sl(tv), sl(tdo) if bwd else None, H, W, win,
+                                     shift, mask, None, wy, wx))
+    for out in outs:
+        bf = out == B.AERIS_DT_BF16
+        o, lse = B.aeris_winattn_fwd(tq, tk, tv, win, shift, mask, out_dtype=out)
         if bwd:
-            # O reaches the backward pass in bf16 here: dQ, dK get the plain tolerance plus
-            # the delta-perturbation bound (see test_config2_smooth_bf16_handover)
-            qw, kw, vw, dow = sl(tq)[y, x], sl(tk)[y, x], sl(tv)[y, x], sl(tdo)[y, x]
-            _, _, yh, xh = orc.window_tokens(H, W, win, shift, wy, wx)
-            reg = orc.token_regions(H, W, win, shift, mask, yh, xh)
-            bq, bk = handover_bounds(qw, kw, vw, dow, reg, 1.0 / np.sqrt(d))
-            check_with_bound("dq", to_f64(dq[b, :, :, h, :])[y, x], res["dq"], bq)
-            check_with_bound("dk", to_f64(dk[b, :, :, h, :])[y, x], res["dk"], bk)
-            check("dv", to_f64(dv[b, :, :, h, :])[y, x], res["dv"], True)
+            dq, dk, dv = B.aeris_winattn_bwd(tq, tk, tv, o, lse, tdo, win, shift, mask,
+                                             out_dtype=out)
+        torch.cuda.synchronize()
+        assert torch.isfinite(o.view(-1)[:: 997].float()).all()
+        # whole-grid properties that hold at any size
+        vmin = tv.amin(dim=(1, 2)).float()
+        vmax = tv.amax(dim=(1, 2)).float()
+        assert (o.amax(dim=(1, 2)).float() <= vmax + 1e-2).all()
+        assert (o.amin(dim=(1, 2)).float() >= vmin - 1e-2).all()
+        if bwd:
+            for b in range(Bn):
+                s_dv = rows_sum(lambda r: dv[b, r].double().sum(dim=(0, 1)), H)
+                s_do = rows_sum(lambda r: tdo[b, r].double().sum(dim=(0, 1)), H)
+                scale_ = rows_sum(lambda r: dv[b, r].double().abs().sum(dim=(0, 1)), H)
+                assert ((s_dv - s_do).abs() <= 2e-3 * scale_ + 1e-2).all()
+                qa = rows_sum(lambda r: (tq[b, r].double() * dq[b, r].double()).sum(dim=(0, 1, 3)), H)
+                kb = rows_sum(lambda r: (tk[b, r].double() * dk[b, r].double()).sum(dim=(0, 1, 3)), H)
+                mag = rows_sum(lambda r: (tq[b, r].double() * dq[b, r].double()).abs().sum(dim=(0, 1, 3)), H)
+                assert ((qa - kb).abs() <= 5e-3 * mag + 1e-2).all()
+        for (b, wy, wx, h), res in zip(samples, refs):
+            sl = lambda t: to_f64(t[b, :, :, h, :])
+            y, x = res["y"], res["x"]
+            wide = bf or (sigmas is not None and sigmas[b] > 1.0)
+            check("o", sl(o)[y, x], res["o"], bf, wide)
+            check_lse(to_f64(lse[b, h])[y, x], res["lse"])
+            if not bwd:
+                continue
+            check("dv", sl(dv)[y, x], res["dv"], bf, wide)
+            if bf:
+                qw, kw, vw, dow = sl(tq)[y, x], sl(tk)[y, x], sl(tv)[y, x], sl(tdo)[y, x]
+                _, _, yh, xh = orc.window_tokens(H, W, win, shift, wy, wx)
+                reg = orc.token_regions(H, W, win, shift, mask, yh, xh)
+                bq, bk = handover_bounds(qw, kw, vw, dow, reg, 1.0 / np.sqrt(d))
+                check_with_bound("dq", sl(dq)[y, x], res["dq"], bq)
+                check_with_bound("dk", sl(dk)[y, x], res["dk"], bk)
+            else:
+                check("dq", sl(dq)[y, x], res["dq"], False, wide)
+                check("dk", sl(dk)[y, x], res["dk"], False, wide)
+        del o, lse
+        if bwd:
+            del dq, dk, dv
+        torch.cuda.empty_cache()
 
 
 def test_config3_quarter_degree_forward_sampled():
@@ -398,7 +459,7 @@ def test_very_peaked_rows_exercise_the_running_maximum(d):
     o, lse = B.aeris_winattn_fwd(tq, tk, tv, win, shift, mask, scale, out_dtype=B.AERIS_DT_F32)
     torch.cuda.synchronize()
     check("o", o, o_ref, False)
-    assert (np.abs(to_f64(lse) - lse_ref) <= LSE_ABS + 1e-5 * np.abs(lse_ref)).all()
+    check_lse(lse, lse_ref, rel=1e-5)
 
 
 @pytest.mark.parametrize("order", ["rising", "falling", "all_low", "late_spike"])
@@ -434,4 +495,4 @@ def test_forward_reference_point_under_monotone_and_extreme_logits(order):
                                  out_dtype=B.AERIS_DT_F32)
     torch.cuda.synchronize()
     check("o", o, o_ref, False)
-    assert (np.abs(to_f64(lse) - lse_ref) <= LSE_ABS + 1e-5 * np.abs(lse_ref)).all()
+    check_lse(lse, lse_ref, rel=1e-5)

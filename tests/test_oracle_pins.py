@@ -361,3 +361,66 @@ def test_unmasked_pair_formula_general_shift():
         assert orc.unmasked_pairs(H, W, (ws, ws), (s, s), orc.MASK_LAT) == round(lat)
         assert orc.unmasked_pairs(H, W, (ws, ws), (s, s), orc.MASK_SWIN) == round(swin)
         assert orc.unmasked_pairs(H, W, (ws, ws), (s, s), orc.MASK_NONE) == nwy * nwx * T2
+
+
+# ----------------------------------------------------------------------------
+# 9. the sampled-pair entry (what the full-size GPU cases are compared with) is the
+#    whole-grid oracle restricted to one (batch, window, head); and an independent
+#    brute-force pin that does not go through the whole-grid functions at all
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("mask", POLICIES)
+@pytest.mark.parametrize("with_do", [False, True])
+def test_sampled_pair_equals_whole_grid_slices(mask, with_do):
+    """Non-square grid and window, unequal shifts: a swapped wy/wx, H/W or slice order,
+    a wrong default scale or a wrong key in the result would all show."""
+    shape, win, shift = (2, 8, 15, 3, 4), (4, 5), (1, 3)
+    Bn, H, W, nh, d = shape
+    q, k, v, do = rand_qkv(71, shape, 4)
+    for scale in (None, 0.37):
+        o, lse = orc.winattn_fwd(q, k, v, win, shift, mask, scale)
+        dq, dk, dv, delta = orc.winattn_bwd(q, k, v, do, win, shift, mask, scale)
+        for b, h in itertools.product(range(Bn), range(nh)):
+            for wy, wx in itertools.product(range(H // win[0]), range(W // win[1])):
+                res = orc.winattn_pair(q[b, :, :, h], k[b, :, :, h], v[b, :, :, h],
+                                       do[b, :, :, h] if with_do else None, H, W, win, shift,
+                                       mask, scale, wy, wx)
+                y, x = res["y"], res["x"]
+                # the window's grid points, built here by hand
+                ey = [(wy * win[0] + r + shift[0]) % H for r in range(win[0]) for _ in range(win[1])]
+                ex = [(wx * win[1] + c + shift[1]) % W for _ in range(win[0]) for c in range(win[1])]
+                assert list(y) == ey and list(x) == ex
+                np.testing.assert_allclose(res["o"], o[b, y, x, h], rtol=0, atol=1e-13)
+                np.testing.assert_allclose(res["lse"], lse[b, h, y, x], rtol=0, atol=1e-13)
+                if with_do:
+                    np.testing.assert_allclose(res["dq"], dq[b, y, x, h], rtol=0, atol=1e-13)
+                    np.testing.assert_allclose(res["dk"], dk[b, y, x, h], rtol=0, atol=1e-13)
+                    np.testing.assert_allclose(res["dv"], dv[b, y, x, h], rtol=0, atol=1e-13)
+                    np.testing.assert_allclose(res["delta"], delta[b, h, y, x], rtol=0, atol=1e-13)
+                else:
+                    assert set(res) == {"y", "x", "o", "lse"}
+
+
+@pytest.mark.parametrize("wy,wx", [(0, 0), (1, 0), (0, 2), (1, 2)])
+def test_sampled_pair_against_brute_force(wy, wx):
+    """Interior, lat-seam, lon-seam and corner window of a SWIN-masked shifted grid against the
+    scalar-loop brute force (which rolls, slices and paints labels: no shared step)."""
+    shape, win, shift = (1, 8, 12, 2, 3), (4, 4), (2, 1)
+    q, k, v = rand_qkv(72, shape)
+    ob, lb = brute_fwd(q, k, v, win, shift, orc.MASK_SWIN, 0.7)
+    res = orc.winattn_pair(q[0, :, :, 1], k[0, :, :, 1], v[0, :, :, 1], None, 8, 12, win, shift,
+                           orc.MASK_SWIN, 0.7, wy, wx)
+    np.testing.assert_allclose(res["o"], ob[0, res["y"], res["x"], 1], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(res["lse"], lb[0, 1, res["y"], res["x"]], rtol=0, atol=1e-12)
+
+
+def test_bench_flop_count_uses_the_oracle_pair_count():
+    """bench.py credits FLOPs per unmasked (query, key) pair through a closed form of its own;
+    it must agree with the oracle's enumeration for general, one-axis and zero shifts."""
+    import bench
+    for (H, W, win) in [(12, 20, (4, 4)), (12, 18, (4, 6)), (8, 8, (8, 8))]:
+        for shift in [(0, 0), (1, 0), (0, 3), (2, 2), (3, 1)]:
+            if shift[0] >= win[0] or shift[1] >= win[1]:
+                continue
+            for mask in POLICIES:
+                want = orc.unmasked_pairs(H, W, win, shift, mask)
+                assert abs(bench.unmasked_pairs(H, W, win, shift, mask) - want) < 1e-6 * want

@@ -171,19 +171,3 @@ def test_backward_finite_differences_shifted_masked_windows():
         e[idx] = eps
         assert abs((loss(q + e, k) - loss(q - e, k)) / (2 * eps) - dq[idx]) < 1e-6
         assert abs((loss(q, k + e) - loss(q, k - e)) / (2 * eps) - dk[idx]) < 1e-6
-
-
-def test_round_hook_is_applied_to_rotated_operands_only():
-    B, H, W, nh, d = 1, 4, 4, 1, 4
-    q, k, v = rng_fields(12, (B, H, W, nh, d), 3)
-    seen = []
-
-    def hook(x):
-        seen.append(x.copy())
-        return x
-
-    ro.winattn_rope_fwd(q, k, v, (2, 2), (0, 0), wa.MASK_NONE, 100.0, ro.POS_GRID, round_fn=hook)
-    phi = ro.angles(H, W, d, (2, 2), (0, 0), 100.0, ro.POS_GRID)
-    assert len(seen) == 2
-    np.testing.assert_array_equal(seen[0], ro.rotate(q, phi))
-    np.testing.assert_array_equal(seen[1], ro.rotate(k, phi))
