@@ -35,9 +35,12 @@
  * The caller owns every buffer.  The library allocates nothing, frees nothing
  * and never synchronises: every call only enqueues kernels on `hip_stream`
  * (a hipStream_t passed as void*; NULL is the default stream).  Inputs are
- * read-only, outputs are fully overwritten.  Calls are thread-safe; there is
- * no global state.  Arguments are validated before anything is launched, so
- * every error except AERIS_ERR_HIP_LAUNCH is reachable without a GPU.
+ * read-only, outputs are fully overwritten.  Calls are thread-safe.  The only
+ * process-wide state is a per-device flag per kernel ("this kernel may use the
+ * whole LDS", set on the first launch on that device; not valid across
+ * hipDeviceReset) and, for aeris_winattn_bwd_static alone, its static scratch
+ * array.  Arguments are validated before anything is launched, so every error
+ * except AERIS_ERR_HIP_LAUNCH and AERIS_ERR_HIP_SYMBOL is reachable without a GPU.
  */
 #ifndef AERIS_WINATTN_H
 #define AERIS_WINATTN_H
@@ -64,8 +67,12 @@ enum {
   AERIS_ERR_WORKSPACE_TOO_SMALL = -8,
   AERIS_ERR_WINDOW_TOO_LARGE = -9,     /* win_h*win_w > AERIS_MAX_WINDOW_TOKENS     */
   AERIS_ERR_BAD_DTYPE = -10,
-  AERIS_ERR_HIP_LAUNCH = -11,          /* hipGetLastError() after a launch          */
-  AERIS_ERR_BAD_ROPE = -12             /* rotary base <= 1 or unknown position mode */
+  AERIS_ERR_HIP_LAUNCH = -11,          /* the launch call reported an error         */
+  AERIS_ERR_BAD_ROPE = -12,            /* rotary base <= 1 or unknown position mode */
+  AERIS_ERR_STATIC_SCRATCH_TOO_SMALL = -13, /* aeris_winattn_bwd_static: problem too large */
+  AERIS_ERR_HIP_SYMBOL = -14           /* aeris_winattn_bwd_static: no device address of its
+                                          scratch array (hipGetSymbolAddress failed, or device
+                                          ordinal >= 64)                            */
 };
 
 /* Largest window (tokens) the kernels' on-chip offset table holds. */
@@ -121,6 +128,27 @@ int aeris_winattn_bwd(const aeris_winattn_params* p, const void* q, const void* 
                       const void* v, const void* o, const float* lse, const void* d_o,
                       void* dq, void* dk, void* dv, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
+
+/*
+ * aeris_winattn_bwd for callers that cannot allocate or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the kernels' scratch -- the
+ * two per-token statistics vectors that aeris_winattn_bwd keeps in `workspace` -- lives in a
+ * static device array of AERIS_BWD_STATIC_SCRATCH_BYTES inside the library (one copy per GPU,
+ * held until the process ends).  The call allocates nothing, frees nothing and only enqueues
+ * the same kernels on `hip_stream`; results are bit-identical to aeris_winattn_bwd.
+ * Arguments as aeris_winattn_bwd without the workspace.  Problems whose
+ * aeris_winattn_bwd_workspace_bytes(p) exceeds AERIS_BWD_STATIC_SCRATCH_BYTES (8 bytes per
+ * token and head: about 8.3 million (token, head) entries, e.g. 97 windows of 60x60 x 24
+ * heads) are rejected with AERIS_ERR_STATIC_SCRATCH_TOO_SMALL before anything is launched.
+ * The first call on a device looks up the array's device address (hipGetSymbolAddress, no
+ * allocation); make that call outside a graph capture.  All calls on one GPU share the one
+ * array: calls that overlap in time on the same GPU (different streams or threads) race and
+ * must be serialised by the caller; the array's contents are undefined between calls.
+ */
+#define AERIS_BWD_STATIC_SCRATCH_BYTES (64u << 20)
+int aeris_winattn_bwd_static(const aeris_winattn_params* p, const void* q, const void* k,
+                             const void* v, const void* o, const float* lse, const void* d_o,
+                             void* dq, void* dk, void* dv, void* hip_stream);
 
 /* The backward pass has three stages; this variant runs a subset, in the order
  * delta, dq, dkdv (for profiling one kernel, or to put dq and dkdv on different

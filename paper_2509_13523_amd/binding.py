@@ -14,9 +14,10 @@ AERIS_MASK_NONE, AERIS_MASK_LAT, AERIS_MASK_SWIN = 0, 1, 2
 AERIS_DT_BF16, AERIS_DT_F32 = 0, 1
 AERIS_BWD_DELTA, AERIS_BWD_DQ, AERIS_BWD_DKDV, AERIS_BWD_ALL = 1, 2, 4, 7
 AERIS_ROPE_POS_WINDOW, AERIS_ROPE_POS_GRID = 0, 1
+AERIS_BWD_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = ("aeris_winattn_fwd", "aeris_winattn_bwd", "aeris_winattn_bwd_stages",
-           "aeris_winattn_bwd_workspace_bytes",
+           "aeris_winattn_bwd_workspace_bytes", "aeris_winattn_bwd_static",
            "aeris_winattn_validate", "aeris_winattn_strerror", "aeris_winattn_version",
            "aeris_winattn_fwd_windows", "aeris_winattn_bwd_windows",
            "aeris_mfma_loop_probe", "aeris_rope2d_apply", "aeris_winattn_rope_fwd_workspace_bytes",
@@ -71,6 +72,8 @@ def load():
     lib.aeris_winattn_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                       ctypes.c_size_t, vp]
     lib.aeris_winattn_bwd.restype = ctypes.c_int
+    lib.aeris_winattn_bwd_static.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.aeris_winattn_bwd_static.restype = ctypes.c_int
     lib.aeris_winattn_bwd_stages.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                              ctypes.c_size_t, vp, ctypes.c_uint]
     lib.aeris_winattn_bwd_stages.restype = ctypes.c_int
@@ -219,6 +222,30 @@ def aeris_winattn_bwd_stages(q, k, v, o, lse, d_o, win, shift, mask=AERIS_MASK_N
         rc = lib.aeris_winattn_bwd_stages(*args, stages)
     if rc != 0:
         raise AerisError(rc, "aeris_winattn_bwd")
+    return dq, dk, dv
+
+
+def aeris_winattn_bwd_static(q, k, v, o, lse, d_o, win, shift, mask=AERIS_MASK_NONE, scale=None,
+                             out_dtype=AERIS_DT_BF16, dq=None, dk=None, dv=None):
+    """aeris_winattn_bwd with the kernels' scratch in the library's static device array: the
+    C call allocates nothing.  Pass dq, dk, dv to keep torch from allocating them here."""
+    import torch
+    p = make_params(q.shape, win, shift, mask, scale, out_dtype)
+    odt = _torch_out_dtype(out_dtype)
+    assert o.dtype == odt and d_o.dtype == torch.bfloat16 and lse.dtype == torch.float32
+    for t in (q, k, v, o, d_o, lse):
+        assert t.is_cuda and t.is_contiguous()
+    if dq is None:
+        dq = torch.empty(q.shape, dtype=odt, device=q.device)
+    if dk is None:
+        dk = torch.empty(q.shape, dtype=odt, device=q.device)
+    if dv is None:
+        dv = torch.empty(q.shape, dtype=odt, device=q.device)
+    rc = load().aeris_winattn_bwd_static(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                         o.data_ptr(), lse.data_ptr(), d_o.data_ptr(),
+                                         dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_winattn_bwd_static")
     return dq, dk, dv
 
 

@@ -5,7 +5,15 @@
 
 #include <math.h>
 
+#include <atomic>
+
 #include "winattn_launch.hpp"
+
+// Scratch of aeris_winattn_bwd_static: the backward kernels' per-token statistics (delta and
+// LSE * log2 e), which the other backward entry points keep in the caller's workspace.  One copy
+// per GPU the library is loaded on, held until the process ends.  In host code this name is only
+// a handle for hipGetSymbolAddress; kernels receive the device address that call returns.
+static __device__ __align__(256) unsigned char scratch[AERIS_BWD_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -206,6 +214,46 @@ int aeris_winattn_bwd_stages(const aeris_winattn_params* p, const void* q, const
   return AERIS_OK;
 }
 
+// Device address of `scratch` on the current device, looked up once per device.
+static int static_scratch_address(float** out) {
+  static std::atomic<void*> address[aeris::kMaxTrackedDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= aeris::kMaxTrackedDevices)
+    return AERIS_ERR_HIP_SYMBOL;
+  void* ptr = address[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr)
+      return AERIS_ERR_HIP_SYMBOL;
+    address[dev].store(ptr, std::memory_order_release);
+  }
+  *out = static_cast<float*>(ptr);
+  return AERIS_OK;
+}
+
+int aeris_winattn_bwd_static(const aeris_winattn_params* p, const void* q, const void* k,
+                             const void* v, const void* o, const float* lse, const void* d_o,
+                             void* dq, void* dk, void* dv, void* hip_stream) {
+  Strides s;
+  int rc = resolve(p, &s);
+  if (rc != AERIS_OK) return rc;
+  if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv) return AERIS_ERR_NULL_POINTER;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) ||
+      misaligned(d_o) || misaligned(dq) || misaligned(dk) || misaligned(dv))
+    return AERIS_ERR_MISALIGNED;
+  const aeris::KParams kp = derive(p, s);
+  if (aeris::bwd_workspace_bytes(kp) > (size_t)AERIS_BWD_STATIC_SCRATCH_BYTES)
+    return AERIS_ERR_STATIC_SCRATCH_TOO_SMALL;
+  float* stats = nullptr;
+  rc = static_scratch_address(&stats);
+  if (rc != AERIS_OK) return rc;
+  // Nothing in the array has to start at zero: the dQ kernel writes every statistic the dK/dV
+  // kernel reads (all tokens of all pairs plus the padding behind the last pair) in this call.
+  if (aeris::launch_bwd(kp, p->head_dim, p->out_dtype == AERIS_DT_F32, q, k, v, o, lse, d_o, dq,
+                        dk, dv, stats, static_cast<hipStream_t>(hip_stream), AERIS_BWD_ALL) != 0)
+    return AERIS_ERR_HIP_LAUNCH;
+  return AERIS_OK;
+}
+
 int aeris_rope2d_apply(const aeris_winattn_params* p, const aeris_rope_params* r, const void* x,
                        void* y, int32_t inverse, void* hip_stream) {
   Strides s;
@@ -371,10 +419,13 @@ const char* aeris_winattn_strerror(int code) {
     case AERIS_ERR_BAD_DTYPE: return "unknown output dtype";
     case AERIS_ERR_HIP_LAUNCH: return "HIP kernel launch failed";
     case AERIS_ERR_BAD_ROPE: return "rotary base must be > 1 and the position mode known";
+    case AERIS_ERR_STATIC_SCRATCH_TOO_SMALL:
+      return "problem needs more backward scratch than AERIS_BWD_STATIC_SCRATCH_BYTES";
+    case AERIS_ERR_HIP_SYMBOL: return "address of the static scratch array not available on this device";
   }
   return "unknown error code";
 }
 
-int aeris_winattn_version(void) { return 120; }
+int aeris_winattn_version(void) { return 2 * 10000 + 0 * 100 + 0; }
 
 }  // extern "C"

@@ -24,9 +24,10 @@ def test_exports_match_header():
 
 
 def test_version_and_strerror():
-    assert B.aeris_winattn_version() >= 100
+    v = B.aeris_winattn_version()          # major * 10000 + minor * 100 + patch
+    assert v >= 20000 and v % 100 < 100 and (v // 100) % 100 < 100
     assert B.aeris_winattn_strerror(0) == "ok"
-    for code in range(-12, 0):
+    for code in range(-14, 0):
         assert B.aeris_winattn_strerror(code) != "unknown error code"
     assert B.aeris_winattn_strerror(-99) == "unknown error code"
 
@@ -74,6 +75,29 @@ def test_null_and_misaligned_pointers_rejected_before_launch():
     bad = B.make_params(**dict(good(), win=(7, 8)))
     assert B.aeris_winattn_bwd_workspace_bytes(bad) == 0
     assert lib.aeris_winattn_bwd(ctypes.byref(bad), *args, need, None) == -3
+
+
+def test_static_scratch_backward_rejects_before_launch():
+    """The allocation-free backward validates like aeris_winattn_bwd and refuses problems whose
+    statistics do not fit its static array, all before any HIP call."""
+    lib = B.load()
+    fake = 0x1000
+    args = [fake] * 9
+    p = B.make_params(**good())
+    assert lib.aeris_winattn_bwd_static(None, *args, None) == -1
+    assert lib.aeris_winattn_bwd_static(ctypes.byref(p), *args[:8], None, None) == -1
+    assert lib.aeris_winattn_bwd_static(ctypes.byref(p), fake + 2, *args[1:], None) == -7
+    bad = B.make_params(**dict(good(), shift=(8, 0)))
+    assert lib.aeris_winattn_bwd_static(ctypes.byref(bad), *args, None) == -4
+    # 97 windows of 60x60 x 24 heads still fit 64 MiB; 98 do not
+    fits = B.make_params((1, 60, 97 * 60, 24, 128), (60, 60), (30, 30), B.AERIS_MASK_SWIN)
+    assert B.aeris_winattn_bwd_workspace_bytes(fits) <= B.AERIS_BWD_STATIC_SCRATCH_BYTES
+    big = B.make_params((1, 60, 98 * 60, 24, 128), (60, 60), (30, 30), B.AERIS_MASK_SWIN)
+    assert B.aeris_winattn_bwd_workspace_bytes(big) > B.AERIS_BWD_STATIC_SCRATCH_BYTES
+    assert lib.aeris_winattn_bwd_static(ctypes.byref(big), *args, None) == -13
+    header = open(os.path.join(ROOT, "include", "aeris_winattn.h")).read()
+    m = re.search(r"#define AERIS_BWD_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", header)
+    assert int(m.group(1)) << int(m.group(2)) == B.AERIS_BWD_STATIC_SCRATCH_BYTES
 
 
 def test_rope_arguments_rejected_before_launch():
