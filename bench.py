@@ -47,15 +47,36 @@ WORKLOADS = {
                 name="720x1440 grid, 16 heads x 128, 30x30 windows, shift 0/15, SWIN mask"),
 }
 
-# HBM traffic per launch, bytes, from two rocprofv3 --pmc runs of this file (FETCH_SIZE, then
-# WRITE_SIZE, each scaled by what the same counter reads for the --calibrate-copy kernels:
-# factors 2.000 and 1.000); profiles/c5_kernels_and_counters.txt has the commands and numbers.
 # rocprofv3 FETCH_SIZE + WRITE_SIZE of one launch at 4 x 1,036,800 rows x 2048 channels
-# (profiles/layer_ops_kernel_trace.txt)
+# (profiles/layer_ops_kernel_trace.txt; from that profiling session, not from this run)
 LAYER_OPS_TRAFFIC = {"rmsnorm_adaln_fwd": 34.09e9, "rmsnorm_adaln_bwd": 51.04e9,
                      "gate_residual_fwd": 50.97e9, "gate_residual_bwd": 50.98e9,
                      "swiglu_fwd": 25.48e9, "swiglu_bwd": 42.47e9}
-MEASURED_TRAFFIC = {("c5", "fwd"): 74.6e9, ("c5", "dq"): 110.3e9, ("c5", "dkdv"): 113.6e9}
+
+
+def kernel_symbol(stage, head_dim):
+    """Name of the kernel the library launches for a stage (its dispatch rule: the dK/dV stage
+    has a software-pipelined kernel of its own at head_dim 128)."""
+    if stage == "dkdv" and head_dim == 128:
+        return "winattn_dkdv_pipe_kernel"
+    return "winattn_%s_kernel" % stage
+
+
+def profiled_traffic(workload, stage):
+    """HBM bytes per launch of a kernel as the committed rocprofv3 counter summary records them
+    (lines `TRAFFIC <workload> <stage> <bytes>` in profiles/): measured in that profiling
+    session, not in this run, and labelled so.  None when no summary covers the kernel."""
+    path = os.path.join(ROOT, "profiles", "c5_kernels_and_counters.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 4 and f[0] == "TRAFFIC" and f[1] == workload and f[2] == stage:
+                return {"traffic": float(f[3]),
+                        "traffic_source": "profiles/c5_kernels_and_counters.txt (rocprofv3 --pmc "
+                                          "FETCH_SIZE + WRITE_SIZE of an earlier run of this file)"}
+    except OSError:
+        pass
+    return {"traffic": None}
 
 
 def unmasked_pairs(H, W, win, shift, mask):
@@ -73,8 +94,8 @@ def unmasked_pairs(H, W, win, shift, mask):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS) + ["layer_ops"],
                     help="layer_ops: the element-wise kernels of include/aeris_layer_ops.h on the "
                          "headline grid's tokens (a bandwidth figure, not the headline metric)")
@@ -152,35 +173,51 @@ def main():
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
+    step_marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    step_marks[0].record()
+    for i in range(args.steps):
         step(True)
+        step_marks[i + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
     value = model_flops / (ms_per_step * 1e-3) / 1e12
+    step_ms = sorted(a.elapsed_time(b) for a, b in zip(step_marks, step_marks[1:]))
+
+    def median(xs):
+        xs = sorted(xs)
+        n = len(xs)
+        return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
 
     kern = {}
+    layers = len(wl["layers"])
     for name, evs in events.items():
         if evs:
-            ms = sum(a.elapsed_time(b) for a, b in evs) / len(evs)
+            times = [a.elapsed_time(b) for a, b in evs]
+            ms = sum(times) / len(times)
             kern[name] = {"avg_ms": round(ms, 4), "launches": len(evs)}
+            # median and minimum per layer kind (the masked layer does less work)
+            for li, s in enumerate(wl["layers"]):
+                ts = times[li::layers]
+                kern[name]["shift%d" % s[0]] = {"median_ms": round(median(ts), 4),
+                                                "min_ms": round(min(ts), 4)}
             if kernel_flops[name]:
                 fl = kernel_flops[name] * d * sum(U.values()) / len(U)
                 kern[name]["tflops_executed"] = round(fl / (ms * 1e-3) / 1e12, 2)
     dom = max((k for k in kern if kernel_flops[k]), key=lambda k: kern[k]["avg_ms"] * len(events[k]))
     dom_flops = kernel_flops[dom] * d * sum(U.values()) / len(U)
     achieved = dom_flops / (kern[dom]["avg_ms"] * 1e-3) / 1e12
-    kname = "winattn_dkdv_pipe_kernel" if (dom == "dkdv" and d == 128) else "winattn_%s_kernel" % dom
-    roofline = {"kernel": kname, "bound": "mfma", "achieved": round(achieved, 2),
+    roofline = {"kernel": kernel_symbol(dom, d), "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC.get((args.workload, dom))}
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4)}
+    roofline.update(profiled_traffic(args.workload, dom))
 
     out = {"metric": "window-attn fwd+bwd TFLOP/s (model FLOPs) and % bf16 MFMA peak, "
                      "720x1440 grid, 60x60 win",
            "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+           "ms_per_step_median": round(median(step_ms), 3), "ms_per_step_min": round(step_ms[0], 3),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
            "data": "synthetic", "pct_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
            "config": {"workload": "%s: %s" % (args.workload, wl["name"]),
@@ -315,21 +352,25 @@ def bench_layer_ops(args):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms = {name: sum(a.elapsed_time(b) for a, b in ev[name]) / args.steps for name in ev}
+    ms_min = {name: min(a.elapsed_time(b) for a, b in ev[name]) for name in ev}
     total_bytes = sum(b for _, _, b in ops)
     step_ms = wall * 1e3 / args.steps
-    per_kernel = {name: {"ms": round(ms[name], 3), "GBps": round(b / ms[name] / 1e6, 1)}
+    per_kernel = {name: {"ms": round(ms[name], 3), "min_ms": round(ms_min[name], 3),
+                         "GBps": round(b / ms[name] / 1e6, 1)}
                   for name, _, b in ops}
     slow = max(ops, key=lambda o: ms[o[0]])
     achieved = slow[2] / ms[slow[0]] / 1e6
     result = {"metric": "layer_ops_algorithmic_bandwidth", "value": round(total_bytes / step_ms / 1e6, 1),
               "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
               "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak",
-              "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+              "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
               "config": {"workload": "layer_ops: %d x %d token rows x %d channels (bf16), SwiGLU "
                                      "hidden %d" % (nb, rps, C, C // 2), "kernels": per_kernel},
               "roofline": {"bound": "hbm", "kernel": slow[0], "achieved": round(achieved, 1),
                            "peak": 8000.0, "unit": "GB/s", "frac": round(achieved / 8000.0, 4),
-                           "traffic": LAYER_OPS_TRAFFIC.get(slow[0]) if C == 2048 else None}}
+                           "traffic": LAYER_OPS_TRAFFIC.get(slow[0]) if C == 2048 else None,
+                           "traffic_source": "profiles/layer_ops_kernel_trace.txt (rocprofv3 --pmc, "
+                                             "an earlier run of this file)"}}
     if not args.no_cpu_baseline:
         from oracle import block_oracle as bo
         rows = 4096

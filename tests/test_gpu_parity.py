@@ -35,20 +35,46 @@ def to_f64(t):
     return t.float().cpu().numpy().astype(np.float64)
 
 
-def check(name, got, ref, bf16_out, scale_abs=None):
-    """scale_abs: scale the max-abs bound by max|ref| / 4 (default: bf16 outputs only)."""
-    if scale_abs is None:
-        scale_abs = bf16_out
+def check(name, got, ref, bf16_out, bound=None):
+    """bound: optional element-wise allowance subtracted from the error before the max-abs test
+    (see operand_rounding_bounds); relative L2 is never widened."""
     got = to_f64(got) if isinstance(got, torch.Tensor) else got
     assert np.isfinite(got).all(), name
     # a one-token window has dQ = dK = 0 exactly: allow an absolute floor of 1e-5 per element
-    rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 2e-3 * np.sqrt(ref.size))
+    nref = max(np.linalg.norm(ref), 2e-3 * np.sqrt(ref.size))
+    rel = np.linalg.norm(got - ref) / nref
     err = np.abs(got - ref)
     max_ref = np.abs(ref).max()
-    tol = MAX_ABS * (max(1.0, max_ref / 4.0) if scale_abs else 1.0)
-    parity_log.add(name, "bf16" if bf16_out else "f32", rel, err.max(), max_ref, tol)
+    tol = MAX_ABS * (max(1.0, max_ref / 4.0) if bf16_out else 1.0)
+    parity_log.add(name, "bf16" if bf16_out else "f32", rel, err.max(), max_ref, tol,
+                   None if bound is None else np.linalg.norm(bound) / nref)
     assert rel <= REL_L2, "%s rel_l2 %.3e" % (name, rel)
-    assert err.max() <= tol, "%s max_abs %.3e > %.3e" % (name, err.max(), tol)
+    excess = err if bound is None else np.maximum(err - bound, 0.0)
+    assert excess.max() <= tol, "%s max_abs %.3e > %.3e" % (name, excess.max(), tol)
+
+
+def operand_rounding_bounds(qw, kw, vw, dow, reg, scale):
+    """First-order bounds, per element, on what the kernels' rounding of P and dS to bf16 before
+    the second products does to O, dV, dQ, dK of one (batch, window, head).  Every element of P
+    or dS moves by at most half an ulp, u = 2^-8 relative, so
+        |d O|  <= u P |V|,            |d dV| <= u P^T |dO|,
+        |d delta_i| <= e_i = sum_c |dO_ic| (u P |V|)_ic      (delta is formed from the kernel's O),
+        |d dQ| <= scale (u |dS| |K| + e_i |sum_j P_ij K_j|),
+        |d dK| <= scale (u |dS|^T |Q| + sum_i P_ij e_i |Q_i|),
+    with P, dS from the oracle.  Where operands are far from unit scale and the sums cancel these
+    exceed any fixed absolute bound (an fp64 emulation of exactly these roundings reproduces the
+    GPU's errors on such data)."""
+    u = 2.0 ** -8
+    _, _, P = orc.window_pair_fwd(qw, kw, vw, reg, scale)
+    out = {"o": u * (P @ np.abs(vw))}
+    if dow is not None:
+        dP = dow @ vw.T
+        dS = np.abs(P * (dP - (P * dP).sum(axis=1)[:, None]))
+        e = (np.abs(dow) * out["o"]).sum(axis=1)
+        out["dv"] = u * (P.T @ np.abs(dow))
+        out["dq"] = scale * (u * (dS @ np.abs(kw)) + e[:, None] * np.abs(P @ kw))
+        out["dk"] = scale * (u * (dS.T @ np.abs(qw)) + (P * e[:, None]).T @ np.abs(qw))
+    return out
 
 
 def check_lse(got, ref, rel=0.0):
@@ -70,7 +96,8 @@ def handover_bounds(qw, kw, vw, dow, reg, scale):
 
 
 def check_with_bound(name, got, ref, bound):
-    """bf16 hand-over of O only: the plain tolerance plus the first-order bound above."""
+    """bf16 outputs: the plain tolerance plus an element-wise first-order bound (the bf16
+    hand-over of O, and for far-from-unit-scale operands the operand roundings)."""
     err = np.abs(got - ref)
     assert np.isfinite(got).all(), name
     excess = np.maximum(err - bound, 0.0)
@@ -300,68 +327,89 @@ def sampled_check(shape, win, shift, mask, kind, seed, bwd, samples, sigmas=None
     O reaches the backward pass rounded, and dQ, dK get the plain tolerance plus the
     delta-perturbation bound (see test_config2_smooth_bf16_handover).
 
-    One fp32 case needs the magnitude scaling of the max-abs bound as well: the noise-level-2
-    ensemble member of config 5.  Its operands have a standard deviation of about 2.2 (|V| up to
-    10) and its softmax rows are peaked, so O is close to P_max * V_j with P_max rounded to bf16
-    before the product (2^-9 relative): 2^-9 * 10 = 2e-2 by itself.  Measured: max-abs 2.9e-2 at
-    max|O| = 9.9, relative L2 1.2e-3.  Members whose noise level exceeds 1 are therefore checked
-    with the bound scaled by max|ref| / 4 for fp32 outputs too; every other fp32 comparison in
-    this file is held to the plain 2e-2."""
+    One case needs more: the noise-level-2 ensemble member of config 5.  Its operands have a
+    standard deviation of about 2.2 (|V| up to 10, gradients up to 350) and its softmax rows are
+    peaked, so the rounding of P and dS to bf16 before the second products (2^-9 relative per
+    element; sums that cancel; delta formed from the kernel's own O) moves single elements by
+    more than any fixed absolute bound:
+    measured with fp32 outputs, O max-abs 2.9e-2 at max|O| = 9.9 and dQ 2.1e-1 at max|dQ| = 35,
+    relative L2 1.2e-3 and 3.1e-3.  For members whose noise level exceeds 1 the max-abs test
+    therefore allows, element by element, the first-order effect of those two roundings
+    (operand_rounding_bounds) on top of the plain 2e-2; relative L2 stays 5e-3.  Every other
+    fp32 comparison in this file is held to the plain numbers."""
     Bn, H, W, nh, d = shape
     torch.cuda.empty_cache()
-    tensors = synth.make_inputs_device(kind, seed, shape, 4 if bwd else 3, sigmas=sigmas)
-    tq, tk, tv = tensors[:3]
-    tdo = tensors[3] if bwd else None
-    refs = []
+    T = {}     # every device tensor lives here, so a failing check cannot keep them allocated
+    try:
+        _sampled_check(T, shape, win, shift, mask, kind, seed, bwd, samples, sigmas, outs)
+    finally:
+        T.clear()
+        torch.cuda.empty_cache()
+
+
+def _sampled_check(T, shape, win, shift, mask, kind, seed, bwd, samples, sigmas, outs):
+    Bn, H, W, nh, d = shape
+    scale = 1.0 / np.sqrt(d)
+    names = ("q", "k", "v", "do") if bwd else ("q", "k", "v")
+    T.update(zip(names, synth.make_inputs_device(kind, seed, shape, len(names), sigmas=sigmas)))
+    refs, bounds, handover = [], [], []
     for (b, wy, wx, h) in samples:
         sl = lambda t: to_f64(t[b, :, :, h, :])
-        refs.append(orc.winattn_pair(sl(tq), sl(tk), sl(tv), sl(tdo) if bwd else None, H, W, win,
-                                     shift, mask, None, wy, wx))
+        res = orc.winattn_pair(sl(T["q"]), sl(T["k"]), sl(T["v"]), sl(T["do"]) if bwd else None,
+                               H, W, win, shift, mask, None, wy, wx)
+        refs.append(res)
+        y, x = res["y"], res["x"]
+        qw, kw, vw = sl(T["q"])[y, x], sl(T["k"])[y, x], sl(T["v"])[y, x]
+        dow = sl(T["do"])[y, x] if bwd else None
+        _, _, yh, xh = orc.window_tokens(H, W, win, shift, wy, wx)
+        reg = orc.token_regions(H, W, win, shift, mask, yh, xh)
+        wide = sigmas is not None and sigmas[b] > 1.0
+        bounds.append(operand_rounding_bounds(qw, kw, vw, dow, reg, scale) if wide else None)
+        handover.append(handover_bounds(qw, kw, vw, dow, reg, scale) if bwd else None)
     for out in outs:
         bf = out == B.AERIS_DT_BF16
-        o, lse = B.aeris_winattn_fwd(tq, tk, tv, win, shift, mask, out_dtype=out)
+        T["o"], T["lse"] = B.aeris_winattn_fwd(T["q"], T["k"], T["v"], win, shift, mask,
+                                               out_dtype=out)
         if bwd:
-            dq, dk, dv = B.aeris_winattn_bwd(tq, tk, tv, o, lse, tdo, win, shift, mask,
-                                             out_dtype=out)
+            T["dq"], T["dk"], T["dv"] = B.aeris_winattn_bwd(
+                T["q"], T["k"], T["v"], T["o"], T["lse"], T["do"], win, shift, mask, out_dtype=out)
         torch.cuda.synchronize()
-        assert torch.isfinite(o.view(-1)[:: 997].float()).all()
+        assert torch.isfinite(T["o"].view(-1)[:: 997].float()).all()
         # whole-grid properties that hold at any size
-        vmin = tv.amin(dim=(1, 2)).float()
-        vmax = tv.amax(dim=(1, 2)).float()
-        assert (o.amax(dim=(1, 2)).float() <= vmax + 1e-2).all()
-        assert (o.amin(dim=(1, 2)).float() >= vmin - 1e-2).all()
+        vmin = T["v"].amin(dim=(1, 2)).float()
+        vmax = T["v"].amax(dim=(1, 2)).float()
+        assert (T["o"].amax(dim=(1, 2)).float() <= vmax + 1e-2).all()
+        assert (T["o"].amin(dim=(1, 2)).float() >= vmin - 1e-2).all()
         if bwd:
             for b in range(Bn):
-                s_dv = rows_sum(lambda r: dv[b, r].double().sum(dim=(0, 1)), H)
-                s_do = rows_sum(lambda r: tdo[b, r].double().sum(dim=(0, 1)), H)
-                scale_ = rows_sum(lambda r: dv[b, r].double().abs().sum(dim=(0, 1)), H)
+                dsum = lambda t, r: t[b, r].double().sum(dim=(0, 1))
+                s_dv = rows_sum(lambda r: dsum(T["dv"], r), H)
+                s_do = rows_sum(lambda r: dsum(T["do"], r), H)
+                scale_ = rows_sum(lambda r: T["dv"][b, r].double().abs().sum(dim=(0, 1)), H)
                 assert ((s_dv - s_do).abs() <= 2e-3 * scale_ + 1e-2).all()
-                qa = rows_sum(lambda r: (tq[b, r].double() * dq[b, r].double()).sum(dim=(0, 1, 3)), H)
-                kb = rows_sum(lambda r: (tk[b, r].double() * dk[b, r].double()).sum(dim=(0, 1, 3)), H)
-                mag = rows_sum(lambda r: (tq[b, r].double() * dq[b, r].double()).abs().sum(dim=(0, 1, 3)), H)
+                dot = lambda a, g, r: (a[b, r].double() * g[b, r].double())
+                qa = rows_sum(lambda r: dot(T["q"], T["dq"], r).sum(dim=(0, 1, 3)), H)
+                kb = rows_sum(lambda r: dot(T["k"], T["dk"], r).sum(dim=(0, 1, 3)), H)
+                mag = rows_sum(lambda r: dot(T["q"], T["dq"], r).abs().sum(dim=(0, 1, 3)), H)
                 assert ((qa - kb).abs() <= 5e-3 * mag + 1e-2).all()
-        for (b, wy, wx, h), res in zip(samples, refs):
+        for (b, wy, wx, h), res, bnd, hand in zip(samples, refs, bounds, handover):
             sl = lambda t: to_f64(t[b, :, :, h, :])
             y, x = res["y"], res["x"]
-            wide = bf or (sigmas is not None and sigmas[b] > 1.0)
-            check("o", sl(o)[y, x], res["o"], bf, wide)
-            check_lse(to_f64(lse[b, h])[y, x], res["lse"])
+            get = lambda name: None if bnd is None else bnd[name]
+            check("o", sl(T["o"])[y, x], res["o"], bf, get("o"))
+            check_lse(to_f64(T["lse"][b, h])[y, x], res["lse"])
             if not bwd:
                 continue
-            check("dv", sl(dv)[y, x], res["dv"], bf, wide)
+            check("dv", sl(T["dv"])[y, x], res["dv"], bf, get("dv"))
             if bf:
-                qw, kw, vw, dow = sl(tq)[y, x], sl(tk)[y, x], sl(tv)[y, x], sl(tdo)[y, x]
-                _, _, yh, xh = orc.window_tokens(H, W, win, shift, wy, wx)
-                reg = orc.token_regions(H, W, win, shift, mask, yh, xh)
-                bq, bk = handover_bounds(qw, kw, vw, dow, reg, 1.0 / np.sqrt(d))
-                check_with_bound("dq", sl(dq)[y, x], res["dq"], bq)
-                check_with_bound("dk", sl(dk)[y, x], res["dk"], bk)
+                extra = (0.0, 0.0) if bnd is None else (bnd["dq"], bnd["dk"])
+                check_with_bound("dq", sl(T["dq"])[y, x], res["dq"], hand[0] + extra[0])
+                check_with_bound("dk", sl(T["dk"])[y, x], res["dk"], hand[1] + extra[1])
             else:
-                check("dq", sl(dq)[y, x], res["dq"], False, wide)
-                check("dk", sl(dk)[y, x], res["dk"], False, wide)
-        del o, lse
-        if bwd:
-            del dq, dk, dv
+                check("dq", sl(T["dq"])[y, x], res["dq"], False, get("dq"))
+                check("dk", sl(T["dk"])[y, x], res["dk"], False, get("dk"))
+        for name in ("o", "lse", "dq", "dk", "dv"):
+            T.pop(name, None)
         torch.cuda.empty_cache()
 
 
