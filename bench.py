@@ -41,6 +41,20 @@ WORKLOADS = {
     "c3": dict(shape=(1, 720, 1440, 16, 64), win=(60, 60), layers=[(30, 30)], mask=2,
                kind="normal", sigmas=None, bwd=False, seed=3000,
                name="720x1440 grid, 16 heads x 64, 60x60 windows, shift 30, forward only"),
+    # the headline workload through the rotary-embedding entry points (Model Architecture
+    # section: queries and keys are rotated before the attention): forward = rotation pass over
+    # K + attention kernel (which rotates Q as it loads it and keeps the rotated rows), backward
+    # from the rotated operands the forward call kept
+    "c5_rope": dict(shape=(4, 720, 1440, 16, 128), win=(60, 60), layers=[(0, 0), (30, 30)],
+                    mask=2, kind="blend", sigmas=[0.1, 0.5, 1.0, 2.0], bwd=True, seed=5000,
+                    rope=(100.0, 0),
+                    name="c5 with axial 2-D RoPE (base 100, window positions) on Q and K"),
+    # one of eight window-parallel ranks of the headline workload (SWiPe section: round-robin
+    # subsets of the windows): every eighth window of the 12 x 24 grid, full-grid tensor layout
+    "c5_share36": dict(shape=(4, 720, 1440, 16, 128), win=(60, 60), layers=[(0, 0), (30, 30)],
+                       mask=2, kind="blend", sigmas=[0.1, 0.5, 1.0, 2.0], bwd=True, seed=5000,
+                       share=(8, 3),
+                       name="c5, windows w = 3 (mod 8) only: 36 of 288 windows (one of 8 ranks)"),
     # the 6-hourly model's windows (Model Architecture section): T = 900, ragged tiles on both sides
     "w30": dict(shape=(1, 720, 1440, 16, 128), win=(30, 30), layers=[(0, 0), (15, 15)], mask=2,
                 kind="blend", sigmas=None, bwd=True, seed=6000,
@@ -91,6 +105,16 @@ def unmasked_pairs(H, W, win, shift, mask):
     return fy * fx * (win[0] * win[1]) ** 2
 
 
+def window_pairs(H, W, win, shift, mask, wy, wx):
+    """Unmasked (query, key) pairs of one window (seam windows see fewer)."""
+    def axis(L, ws, s, masked, idx):
+        if not masked or s == 0 or idx != L // ws - 1:
+            return 1.0
+        return ((ws - s) ** 2 + s ** 2) / ws ** 2
+    return (axis(H, win[0], shift[0], mask in (1, 2), wy) * axis(W, win[1], shift[1], mask == 2, wx)
+            * (win[0] * win[1]) ** 2)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -139,11 +163,23 @@ def main():
         dq, dk, dv = torch.empty_like(tq), torch.empty_like(tq), torch.empty_like(tq)
         p0 = B.make_params(shape, win, (0, 0), mask)
         ws = torch.empty(B.aeris_winattn_bwd_workspace_bytes(p0), dtype=torch.uint8, device=dev)
+    rope, share = wl.get("rope"), wl.get("share")
+    nwx = W // win[1]
+    picks = None
+    if share:
+        picks = [w for w in range((H // win[0]) * nwx) if w % share[0] == share[1]]
+        lst = torch.tensor(picks, dtype=torch.int32, device=dev)
+    if rope:
+        fws = torch.empty(B.aeris_winattn_rope_fwd_workspace_bytes(p0), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
-    U = {s: Bn * nh * unmasked_pairs(H, W, win, s, mask) for s in wl["layers"]}
+    if picks is None:
+        U = {s: Bn * nh * unmasked_pairs(H, W, win, s, mask) for s in wl["layers"]}
+    else:
+        U = {s: Bn * nh * sum(window_pairs(H, W, win, s, mask, w // nwx, w % nwx) for w in picks)
+             for s in wl["layers"]}
     model_flops = sum((12 if wl["bwd"] else 4) * d * U[s] for s in wl["layers"])
-    kernel_flops = {"fwd": 4, "dq": 6, "dkdv": 8}
+    kernel_flops = {"fwd": 4, "dq": 6, "dkdv": 8, "bwd": 14}
     events = {k: [] for k in kernel_flops}
 
     def timed(name, fn, record):
@@ -157,7 +193,24 @@ def main():
         e1.record()
         events[name].append((e0, e1))
 
-    def step(record):
+    def step_calls(record):
+        """Workloads that go through entry points without a per-kernel split: one event pair
+        per call (forward call, backward call)."""
+        for s in wl["layers"]:
+            if rope:
+                timed("fwd", lambda: B.aeris_winattn_rope_fwd(
+                    tq, tk, tv, win, s, rope[0], rope[1], mask, o=o, lse=lse, workspace=fws), record)
+                timed("bwd", lambda: B.aeris_winattn_rope_bwd(
+                    tq, tk, tv, o, lse, tdo, win, s, rope[0], rope[1], mask, workspace=ws,
+                    saved=fws, dq=dq, dk=dk, dv=dv), record)
+            else:
+                timed("fwd", lambda: B.aeris_winattn_fwd_windows(tq, tk, tv, win, s, lst, o, lse,
+                                                                 mask), record)
+                timed("bwd", lambda: B.aeris_winattn_bwd_windows(
+                    tq, tk, tv, o, lse, tdo, win, s, lst, dq, dk, dv, mask=mask, workspace=ws),
+                    record)
+
+    def step_plain(record):
         for s in wl["layers"]:
             timed("fwd", lambda: B.aeris_winattn_fwd(tq, tk, tv, win, s, mask, o=o, lse=lse),
                   record)
@@ -170,6 +223,7 @@ def main():
                         tq, tk, tv, o, lse, tdo, win, s, mask, dq=dq, dk=dk, dv=dv,
                         workspace=ws, stages=st), record)
 
+    step = step_calls if (rope or share) else step_plain
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
@@ -208,10 +262,31 @@ def main():
     dom = max((k for k in kern if kernel_flops[k]), key=lambda k: kern[k]["avg_ms"] * len(events[k]))
     dom_flops = kernel_flops[dom] * d * sum(U.values()) / len(U)
     achieved = dom_flops / (kern[dom]["avg_ms"] * 1e-3) / 1e12
-    roofline = {"kernel": kernel_symbol(dom, d), "bound": "mfma", "achieved": round(achieved, 2),
+    dom_name = (kernel_symbol("dq", d) + " + " + kernel_symbol("dkdv", d) if dom == "bwd"
+                else kernel_symbol(dom, d))
+    roofline = {"kernel": dom_name, "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4)}
     roofline.update(profiled_traffic(args.workload, dom))
+    extra = {}
+    if rope or share:
+        # the same layers through the plain full-grid entry points, timed in this run, so that the
+        # cost of the rotation / the efficiency of a share is a figure of this run
+        step_plain(False)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            step_plain(False)
+        e1.record()
+        torch.cuda.synchronize()
+        plain_ms = e0.elapsed_time(e1) / 3
+        extra["plain_full_grid_ms_per_step"] = round(plain_ms, 3)
+        if rope:
+            extra["rope_overhead_pct"] = round(100 * (ms_per_step / plain_ms - 1), 2)
+        else:
+            extra["share_rate_vs_full_grid"] = round(plain_ms * len(picks) /
+                                                    ((H // win[0]) * nwx) / ms_per_step, 4)
 
     out = {"metric": "window-attn fwd+bwd TFLOP/s (model FLOPs) and % bf16 MFMA peak, "
                      "720x1440 grid, 60x60 win",
@@ -225,9 +300,12 @@ def main():
                       "layers_per_step": len(wl["layers"]),
                       "model_tflop_per_step": round(model_flops / 1e12, 2)},
            "kernels": kern, "roofline": roofline}
+    out.update(extra)
     # algorithmic HBM bytes per step: fwd reads Q,K,V and writes O, LSE; bwd reads Q,K,V,O,dO
     # twice over its three kernels (O,dO; Q,K,V,dO; Q,K,V,dO) and writes dQ,dK,dV
     tensor = 2.0 * Bn * H * W * nh * d
+    if picks is not None:
+        tensor *= len(picks) / ((H // win[0]) * nwx)
     step_bytes = len(wl["layers"]) * ((4 + (13 if wl["bwd"] else 0)) * tensor)
     out["algorithmic_gbs"] = round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1)
 

@@ -216,8 +216,10 @@ typedef struct {
 int aeris_rope2d_apply(const aeris_winattn_params* p, const aeris_rope_params* r, const void* x,
                        void* y, int32_t inverse, void* hip_stream);
 
-/* Bytes of workspace of the two calls below: room for rotated copies of k (forward),
- * of q and k plus the backward workspace (backward).  0 if the parameters are invalid. */
+/* Bytes of workspace of the two calls below.  Forward: room for the rotated keys and the
+ * rotated queries (two compact tensors).  Backward without the forward's saved rotations: room
+ * for rotated copies of q and k plus the backward statistics; with them,
+ * aeris_winattn_bwd_workspace_bytes(p) is enough.  0 if the parameters are invalid. */
 size_t aeris_winattn_rope_fwd_workspace_bytes(const aeris_winattn_params* p);
 size_t aeris_winattn_rope_bwd_workspace_bytes(const aeris_winattn_params* p);
 
@@ -225,9 +227,11 @@ size_t aeris_winattn_rope_bwd_workspace_bytes(const aeris_winattn_params* p);
  * aeris_winattn_fwd on rotated queries and keys: o, lse = attention(R q, R k, v).
  * The keys stream from global memory into the LDS without passing registers, so they
  * are rotated once into the workspace by a memory-bound pass; the queries, which the
- * kernel keeps in registers, are rotated as they are loaded.  Arguments as
- * aeris_winattn_fwd; workspace: >= aeris_winattn_rope_fwd_workspace_bytes(p) bytes,
- * 16-byte aligned, contents undefined before and after.
+ * kernel keeps in registers, are rotated as they are loaded and a copy of the rotated rows
+ * is stored behind the rotated keys.  Arguments as aeris_winattn_fwd; workspace:
+ * >= aeris_winattn_rope_fwd_workspace_bytes(p) bytes, 16-byte aligned.  After the call it
+ * holds [rotated k | rotated q] (compact layout, bf16): pass it unchanged as `saved` to
+ * aeris_winattn_rope_bwd and the backward pass rotates nothing again.
  */
 int aeris_winattn_rope_fwd(const aeris_winattn_params* p, const aeris_rope_params* r,
                            const void* q, const void* k, const void* v, void* o, float* lse,
@@ -236,20 +240,26 @@ int aeris_winattn_rope_fwd(const aeris_winattn_params* p, const aeris_rope_param
 /*
  * Backward of aeris_winattn_rope_fwd: gradients with respect to the UNROTATED q and k
  * (dq = R^T dq', dk = R^T dk', rotated back in the epilogues of the kernels that
- * accumulate them) and v.  q, k are the unrotated inputs; o, lse the outputs of
- * aeris_winattn_rope_fwd.  Other arguments as aeris_winattn_bwd; workspace:
- * >= aeris_winattn_rope_bwd_workspace_bytes(p) bytes.
+ * accumulate them) and v.  o, lse are the outputs of aeris_winattn_rope_fwd.
+ *   saved     : the workspace of the matching aeris_winattn_rope_fwd call, untouched since
+ *               (read-only), or NULL.  With it q and k are not read (they may be NULL) and
+ *               workspace needs aeris_winattn_bwd_workspace_bytes(p) bytes; without it q and
+ *               k are rotated again into the workspace, which then needs
+ *               aeris_winattn_rope_bwd_workspace_bytes(p) bytes.  Same results either way.
+ * Other arguments as aeris_winattn_bwd.
  */
 int aeris_winattn_rope_bwd(const aeris_winattn_params* p, const aeris_rope_params* r,
                            const void* q, const void* k, const void* v, const void* o,
                            const float* lse, const void* d_o, void* dq, void* dk, void* dv,
-                           void* workspace, size_t workspace_bytes, void* hip_stream);
+                           const void* saved, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
 
 /*
  * The two calls above for a listed subset of the windows (SWiPe: a rank's share of the windows
  * runs the same rotary attention): `windows`, `n_windows` as in aeris_winattn_fwd_windows.  Only
- * tokens of the listed windows are rotated, read or written; the workspace has the size of the
- * full-grid calls (the rotated copies keep the full-grid layout).
+ * tokens of the listed windows are rotated, read or written; the workspaces have the size of the
+ * full-grid calls (the rotated copies keep the full-grid layout), and `saved` must come from a
+ * forward call over the same list.
  */
 int aeris_winattn_rope_fwd_windows(const aeris_winattn_params* p, const aeris_rope_params* r,
                                    const int32_t* windows, int32_t n_windows, const void* q,
@@ -258,8 +268,9 @@ int aeris_winattn_rope_fwd_windows(const aeris_winattn_params* p, const aeris_ro
 int aeris_winattn_rope_bwd_windows(const aeris_winattn_params* p, const aeris_rope_params* r,
                                    const int32_t* windows, int32_t n_windows, const void* q,
                                    const void* k, const void* v, const void* o, const float* lse,
-                                   const void* d_o, void* dq, void* dk, void* dv, void* workspace,
-                                   size_t workspace_bytes, void* hip_stream);
+                                   const void* d_o, void* dq, void* dk, void* dv,
+                                   const void* saved, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream);
 
 /*
  * Measurement aid (for callers that report a fraction of the attainable MFMA rate; not part

@@ -101,13 +101,13 @@ def load():
     lib.aeris_winattn_rope_bwd_workspace_bytes.restype = ctypes.c_size_t
     lib.aeris_winattn_rope_fwd.argtypes = [P, R, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.aeris_winattn_rope_fwd.restype = ctypes.c_int
-    lib.aeris_winattn_rope_bwd.argtypes = [P, R, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+    lib.aeris_winattn_rope_bwd.argtypes = [P, R, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                            ctypes.c_size_t, vp]
     lib.aeris_winattn_rope_bwd.restype = ctypes.c_int
     lib.aeris_winattn_rope_fwd_windows.argtypes = [P, R, vp, ctypes.c_int32, vp, vp, vp, vp, vp, vp,
                                                    ctypes.c_size_t, vp]
     lib.aeris_winattn_rope_fwd_windows.restype = ctypes.c_int
-    lib.aeris_winattn_rope_bwd_windows.argtypes = [P, R, vp, ctypes.c_int32, vp, vp, vp, vp, vp, vp,
+    lib.aeris_winattn_rope_bwd_windows.argtypes = [P, R, vp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp,
                                                    vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.aeris_winattn_rope_bwd_windows.restype = ctypes.c_int
     i64, i32, f32, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
@@ -273,8 +273,10 @@ def aeris_winattn_rope_bwd_workspace_bytes(params):
 
 
 def aeris_winattn_rope_fwd(q, k, v, win, shift, base, positions, mask=AERIS_MASK_NONE, scale=None,
-                           out_dtype=AERIS_DT_BF16, o=None, lse=None, workspace=None):
-    """Attention on rotated queries and keys.  Returns (o, lse)."""
+                           out_dtype=AERIS_DT_BF16, o=None, lse=None, workspace=None,
+                           return_saved=False):
+    """Attention on rotated queries and keys.  Returns (o, lse), or (o, lse, workspace) with
+    return_saved: the workspace then holds the rotated k and q for aeris_winattn_rope_bwd."""
     import torch
     B, H, W, nh, d = q.shape
     for t in (q, k, v):
@@ -293,13 +295,14 @@ def aeris_winattn_rope_fwd(q, k, v, win, shift, base, positions, mask=AERIS_MASK
                                        workspace.data_ptr(), workspace.numel(), _stream())
     if rc != 0:
         raise AerisError(rc, "aeris_winattn_rope_fwd")
-    return o, lse
+    return (o, lse, workspace) if return_saved else (o, lse)
 
 
 def aeris_winattn_rope_bwd(q, k, v, o, lse, d_o, win, shift, base, positions,
                            mask=AERIS_MASK_NONE, scale=None, out_dtype=AERIS_DT_BF16,
-                           workspace=None):
-    """Gradients with respect to the unrotated q, k and v.  Returns (dq, dk, dv)."""
+                           workspace=None, saved=None, dq=None, dk=None, dv=None):
+    """Gradients with respect to the unrotated q, k and v.  Returns (dq, dk, dv).  saved: the
+    workspace of the matching forward call (nothing is rotated again)."""
     import torch
     p = make_params(q.shape, win, shift, mask, scale, out_dtype)
     r = aeris_rope_params(float(base), int(positions))
@@ -307,15 +310,17 @@ def aeris_winattn_rope_bwd(q, k, v, o, lse, d_o, win, shift, base, positions,
     assert o.dtype == odt and d_o.dtype == torch.bfloat16 and lse.dtype == torch.float32
     for t in (q, k, v, o, d_o, lse):
         assert t.is_cuda and t.is_contiguous()
-    dq, dk, dv = [torch.empty(q.shape, dtype=odt, device=q.device) for _ in range(3)]
-    need = aeris_winattn_rope_bwd_workspace_bytes(p)
+    dq, dk, dv = [torch.empty(q.shape, dtype=odt, device=q.device) if t is None else t
+                  for t in (dq, dk, dv)]
+    need = (aeris_winattn_rope_bwd_workspace_bytes(p) if saved is None
+            else aeris_winattn_bwd_workspace_bytes(p))
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     rc = load().aeris_winattn_rope_bwd(ctypes.byref(p), ctypes.byref(r), q.data_ptr(),
                                        k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
                                        d_o.data_ptr(), dq.data_ptr(), dk.data_ptr(),
-                                       dv.data_ptr(), workspace.data_ptr(), workspace.numel(),
-                                       _stream())
+                                       dv.data_ptr(), None if saved is None else saved.data_ptr(),
+                                       workspace.data_ptr(), workspace.numel(), _stream())
     if rc != 0:
         raise AerisError(rc, "aeris_winattn_rope_bwd")
     return dq, dk, dv
@@ -382,21 +387,24 @@ def aeris_winattn_rope_fwd_windows(q, k, v, win, shift, base, positions, windows
 
 def aeris_winattn_rope_bwd_windows(q, k, v, o, lse, d_o, win, shift, base, positions, windows,
                                    dq, dk, dv, mask=AERIS_MASK_NONE, scale=None,
-                                   out_dtype=AERIS_DT_BF16, workspace=None):
-    """Backward of the call above; dq, dk, dv are written only inside the listed windows."""
+                                   out_dtype=AERIS_DT_BF16, workspace=None, saved=None):
+    """Backward of the call above; dq, dk, dv are written only inside the listed windows.
+    saved: the workspace of the forward call over the same list."""
     import torch
     assert windows.is_cuda and windows.dtype == torch.int32 and windows.is_contiguous()
     p = make_params(q.shape, win, shift, mask, scale, out_dtype)
     r = aeris_rope_params(float(base), int(positions))
     if workspace is None:
-        workspace = torch.empty(aeris_winattn_rope_bwd_workspace_bytes(p), dtype=torch.uint8,
-                                device=q.device)
+        need = (aeris_winattn_rope_bwd_workspace_bytes(p) if saved is None
+                else aeris_winattn_bwd_workspace_bytes(p))
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     rc = load().aeris_winattn_rope_bwd_windows(ctypes.byref(p), ctypes.byref(r), windows.data_ptr(),
                                                windows.numel(), q.data_ptr(), k.data_ptr(),
                                                v.data_ptr(), o.data_ptr(), lse.data_ptr(),
                                                d_o.data_ptr(), dq.data_ptr(), dk.data_ptr(),
-                                               dv.data_ptr(), workspace.data_ptr(),
-                                               workspace.numel(), _stream())
+                                               dv.data_ptr(),
+                                               None if saved is None else saved.data_ptr(),
+                                               workspace.data_ptr(), workspace.numel(), _stream())
     if rc != 0:
         raise AerisError(rc, "aeris_winattn_rope_bwd_windows")
     return dq, dk, dv

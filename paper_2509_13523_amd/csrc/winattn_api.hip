@@ -79,6 +79,7 @@ aeris::KParams derive(const aeris_winattn_params* p, const Strides& s) {
   k.rope = 0;
   k.rope_pos = 0;
   k.rope_c = 0.f;
+  k.q_rot_out = nullptr;
   return k;
 }
 
@@ -273,7 +274,7 @@ int aeris_rope2d_apply(const aeris_winattn_params* p, const aeris_rope_params* r
 size_t aeris_winattn_rope_fwd_workspace_bytes(const aeris_winattn_params* p) {
   Strides s;
   if (resolve(p, &s) != AERIS_OK) return 0;
-  return dense_tensor_bytes(p);
+  return 2 * dense_tensor_bytes(p);
 }
 
 size_t aeris_winattn_rope_bwd_workspace_bytes(const aeris_winattn_params* p) {
@@ -311,6 +312,10 @@ static int rope_fwd_impl(const aeris_winattn_params* p, const aeris_rope_params*
     return AERIS_ERR_HIP_LAUNCH;
   kp.k_tok = dense_tok;
   kp.k_head = d;
+  // the kernel rotates its resident queries as it loads them and leaves a copy behind the
+  // rotated keys: together they are what the backward pass multiplies with
+  kp.q_rot_out = reinterpret_cast<aeris::bf16_t*>(static_cast<char*>(workspace) +
+                                                  dense_tensor_bytes(p));
   if (aeris::launch_fwd(kp, p->head_dim, p->out_dtype == AERIS_DT_F32, q, workspace, v, o, lse,
                         stream) != 0)
     return AERIS_ERR_HIP_LAUNCH;
@@ -320,39 +325,49 @@ static int rope_fwd_impl(const aeris_winattn_params* p, const aeris_rope_params*
 static int rope_bwd_impl(const aeris_winattn_params* p, const aeris_rope_params* r,
                          const int32_t* windows, int32_t n_windows, bool listed, const void* q,
                          const void* k, const void* v, const void* o, const float* lse,
-                         const void* d_o, void* dq, void* dk, void* dv, void* workspace,
-                         size_t workspace_bytes, void* hip_stream) {
+                         const void* d_o, void* dq, void* dk, void* dv, const void* saved,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
   Strides s;
   int rc = resolve(p, &s);
   if (rc != AERIS_OK) return rc;
   aeris::KParams kp = derive(p, s);
   rc = resolve_rope(p, r, &kp);
   if (rc != AERIS_OK) return rc;
-  if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !workspace)
+  if ((!saved && (!q || !k)) || !v || !o || !lse || !d_o || !dq || !dk || !dv || !workspace)
     return AERIS_ERR_NULL_POINTER;
-  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) ||
-      misaligned(d_o) || misaligned(dq) || misaligned(dk) || misaligned(dv) ||
-      misaligned(workspace))
+  if ((!saved && (misaligned(q) || misaligned(k))) || misaligned(v) || misaligned(o) ||
+      misaligned(lse) || misaligned(d_o) || misaligned(dq) || misaligned(dk) || misaligned(dv) ||
+      misaligned(saved) || misaligned(workspace))
     return AERIS_ERR_MISALIGNED;
   if (listed) {
     rc = restrict_windows(&kp, windows, n_windows);
     if (rc != AERIS_OK) return rc;
   }
-  if (workspace_bytes < aeris_winattn_rope_bwd_workspace_bytes(p))
-    return AERIS_ERR_WORKSPACE_TOO_SMALL;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  // workspace: rotated q | rotated k | statistics of the backward kernels
   const size_t tensor = dense_tensor_bytes(p);
-  char* ws = static_cast<char*>(workspace);
-  void* q_rot = ws;
-  void* k_rot = ws + tensor;
-  float* stats = reinterpret_cast<float*>(ws + 2 * tensor);
+  const size_t need = saved ? aeris::bwd_workspace_bytes(derive(p, s))
+                            : aeris_winattn_rope_bwd_workspace_bytes(p);
+  if (workspace_bytes < need) return AERIS_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const long long d = p->head_dim, dense_tok = (long long)p->heads * d;
-  if (aeris::launch_rope(kp, p->head_dim, q, s.qkv_tok, s.qkv_head, q_rot, dense_tok, d, false,
-                         stream) != 0 ||
-      aeris::launch_rope(kp, p->head_dim, k, s.qkv_tok, s.qkv_head, k_rot, dense_tok, d, false,
-                         stream) != 0)
-    return AERIS_ERR_HIP_LAUNCH;
+  const void *q_rot, *k_rot;
+  float* stats;
+  if (saved) {
+    // what the forward call left in its workspace: rotated k | rotated q
+    k_rot = saved;
+    q_rot = static_cast<const char*>(saved) + tensor;
+    stats = static_cast<float*>(workspace);
+  } else {
+    // workspace: rotated q | rotated k | statistics of the backward kernels
+    char* ws = static_cast<char*>(workspace);
+    q_rot = ws;
+    k_rot = ws + tensor;
+    stats = reinterpret_cast<float*>(ws + 2 * tensor);
+    if (aeris::launch_rope(kp, p->head_dim, q, s.qkv_tok, s.qkv_head, ws, dense_tok, d, false,
+                           stream) != 0 ||
+        aeris::launch_rope(kp, p->head_dim, k, s.qkv_tok, s.qkv_head, ws + tensor, dense_tok, d,
+                           false, stream) != 0)
+      return AERIS_ERR_HIP_LAUNCH;
+  }
   kp.q_tok = kp.k_tok = dense_tok;
   kp.q_head = kp.k_head = d;
   if (aeris::launch_bwd(kp, p->head_dim, p->out_dtype == AERIS_DT_F32, q_rot, k_rot, v, o, lse,
@@ -371,8 +386,9 @@ int aeris_winattn_rope_fwd(const aeris_winattn_params* p, const aeris_rope_param
 int aeris_winattn_rope_bwd(const aeris_winattn_params* p, const aeris_rope_params* r,
                            const void* q, const void* k, const void* v, const void* o,
                            const float* lse, const void* d_o, void* dq, void* dk, void* dv,
-                           void* workspace, size_t workspace_bytes, void* hip_stream) {
-  return rope_bwd_impl(p, r, nullptr, 0, false, q, k, v, o, lse, d_o, dq, dk, dv, workspace,
+                           const void* saved, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
+  return rope_bwd_impl(p, r, nullptr, 0, false, q, k, v, o, lse, d_o, dq, dk, dv, saved, workspace,
                        workspace_bytes, hip_stream);
 }
 
@@ -387,9 +403,9 @@ int aeris_winattn_rope_fwd_windows(const aeris_winattn_params* p, const aeris_ro
 int aeris_winattn_rope_bwd_windows(const aeris_winattn_params* p, const aeris_rope_params* r,
                                    const int32_t* windows, int32_t n_windows, const void* q,
                                    const void* k, const void* v, const void* o, const float* lse,
-                                   const void* d_o, void* dq, void* dk, void* dv, void* workspace,
-                                   size_t workspace_bytes, void* hip_stream) {
-  return rope_bwd_impl(p, r, windows, n_windows, true, q, k, v, o, lse, d_o, dq, dk, dv,
+                                   const void* d_o, void* dq, void* dk, void* dv, const void* saved,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return rope_bwd_impl(p, r, windows, n_windows, true, q, k, v, o, lse, d_o, dq, dk, dv, saved,
                        workspace, workspace_bytes, hip_stream);
 }
 

@@ -56,6 +56,8 @@ struct KParams {
                        //    dq and dk are rotated back as they are stored
   int rope_pos;        // AERIS_ROPE_POS_*
   float rope_c;        // log2(base) / (head_dim / 4): theta_t = 2^(-t * rope_c)
+  bf16_t* q_rot_out;   // forward kernel, rope == 1: if not null, the rotated queries are also
+                       // stored here (compact [B, H, W, heads, head_dim]) for the backward pass
 };
 
 // Bytes of the per-window token table: one int per token, padded to a whole

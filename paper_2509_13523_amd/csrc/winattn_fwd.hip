@@ -83,6 +83,11 @@ __global__ __launch_bounds__(W * 64, W == 4 ? 2 : 1) void winattn_fwd_kernel(
 #pragma unroll
       for (int kk = 0; kk < D / 16; ++kk)
         qreg[kk] = rope_rotate8(qreg[kk], kk * 16 + 8 * g, p_lat, p_lon, p.rope_c, false);
+      if (p.q_rot_out && rg.valid) {   // by-product for the backward pass: no second rotation
+        bf16_t* keep = p.q_rot_out + (((long long)win.b * plane + q_grid) * p.nh + win.head) * D + 8 * g;
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) *reinterpret_cast<bf16x8*>(keep + kk * 16) = qreg[kk];
+      }
     }
   }
   typename Tl::Lanes la;

@@ -116,14 +116,21 @@ def test_rope_arguments_rejected_before_launch():
     assert lib.aeris_rope2d_apply(ctypes.byref(p), None, a, a, 0, None) == -1
     assert lib.aeris_rope2d_apply(ctypes.byref(p), ctypes.byref(r), None, a, 0, None) == -1
     assert lib.aeris_rope2d_apply(ctypes.byref(p), ctypes.byref(r), a + 2, a, 0, None) == -7
-    # workspace sizes: one compact bf16 tensor forward; two of them plus the statistics backward
-    tensor = 1 * 64 * 128 * 4 * 32 * 2
+    # workspace sizes: two compact bf16 tensors forward (rotated k and q, kept for the backward
+    # pass); backward two of them plus the statistics, or the statistics alone with `saved`
+    half = 1 * 64 * 128 * 4 * 32 * 2
+    tensor = 2 * half
+    stats = B.aeris_winattn_bwd_workspace_bytes(p)
     assert B.aeris_winattn_rope_fwd_workspace_bytes(p) == tensor
-    assert B.aeris_winattn_rope_bwd_workspace_bytes(p) == 2 * tensor + B.aeris_winattn_bwd_workspace_bytes(p)
+    assert B.aeris_winattn_rope_bwd_workspace_bytes(p) == 2 * half + stats
     assert lib.aeris_winattn_rope_fwd(ctypes.byref(p), ctypes.byref(r), a, a, a, a, a, a,
                                       tensor - 1, None) == -8
-    assert lib.aeris_winattn_rope_bwd(ctypes.byref(p), ctypes.byref(r), a, a, a, a, a, a, a, a, a,
-                                      a, 2 * tensor, None) == -8
+    P, R = ctypes.byref(p), ctypes.byref(r)
+    assert lib.aeris_winattn_rope_bwd(P, R, a, a, a, a, a, a, a, a, a, None, a, 2 * half, None) == -8
+    assert lib.aeris_winattn_rope_bwd(P, R, a, a, a, a, a, a, a, a, a, a, a, stats - 1, None) == -8
+    assert lib.aeris_winattn_rope_bwd(P, R, None, a, a, a, a, a, a, a, a, None, a, 1 << 40, None) == -1
+    assert lib.aeris_winattn_rope_bwd(P, R, None, None, a, a, a, a, a, a, a, a + 4, a, 1 << 40,
+                                      None) == -7
     # the same calls on a list of windows
     P, R = ctypes.byref(p), ctypes.byref(r)
     assert lib.aeris_winattn_rope_fwd_windows(P, R, None, 4, a, a, a, a, a, a, tensor, None) == -1
@@ -132,10 +139,10 @@ def test_rope_arguments_rejected_before_launch():
     assert lib.aeris_winattn_rope_fwd_windows(P, R, a + 2, 4, a, a, a, a, a, a, tensor, None) == -7
     assert lib.aeris_winattn_rope_fwd_windows(P, R, a, 4, a, a, a, a, a, a, tensor - 1, None) == -8
     assert lib.aeris_winattn_rope_fwd_windows(P, None, a, 4, a, a, a, a, a, a, tensor, None) == -1
-    assert lib.aeris_winattn_rope_bwd_windows(P, R, a, 4, a, a, a, a, a, a, a, a, a, a, 2 * tensor,
-                                              None) == -8
-    assert lib.aeris_winattn_rope_bwd_windows(P, R, a, 4, a, a, a, a, a, a, a, None, a, a, 1 << 40,
-                                              None) == -1
+    assert lib.aeris_winattn_rope_bwd_windows(P, R, a, 4, a, a, a, a, a, a, a, a, a, None, a,
+                                              2 * half, None) == -8
+    assert lib.aeris_winattn_rope_bwd_windows(P, R, a, 4, a, a, a, a, a, a, a, None, a, None, a,
+                                              1 << 40, None) == -1
 
 
 def test_window_list_arguments_rejected_before_launch():
@@ -177,7 +184,7 @@ def test_header_is_plain_c_and_callable_from_c(tmp_path):
     assert got["validate"] == "0"
     assert got["validate_bad"].startswith("-3 window does not divide")
     assert int(got["bwd_ws"]) == 2 * (1 * 128 * 4 * 64 + 64) * 4
-    assert int(got["rope_fwd_ws"]) == 64 * 128 * 4 * 32 * 2
+    assert int(got["rope_fwd_ws"]) == 2 * 64 * 128 * 4 * 32 * 2
     assert got["null_fwd"] == "-1" and got["null_rope"] == "-1"
 
 

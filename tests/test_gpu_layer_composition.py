@@ -96,10 +96,12 @@ def test_attention_half_of_a_layer_forward_and_backward():
     part = lambda t, i: t.data_ptr() + i * C * 2
     ta = torch.empty(N, C, dtype=torch.bfloat16, device="cuda")
     tlse = torch.empty(Bn, nh, H, W, dtype=torch.float32, device="cuda")
-    ws = torch.empty(B.aeris_winattn_rope_bwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    # the forward call's workspace keeps the rotated k and q for the backward call
+    fws = torch.empty(B.aeris_winattn_rope_fwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.aeris_winattn_bwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
     rc = lib.aeris_winattn_rope_fwd(ctypes.byref(p), ctypes.byref(r), part(tqkv, 0), part(tqkv, 1),
-                                    part(tqkv, 2), ta.data_ptr(), tlse.data_ptr(), ws.data_ptr(),
-                                    ws.numel(), stream)
+                                    part(tqkv, 2), ta.data_ptr(), tlse.data_ptr(), fws.data_ptr(),
+                                    fws.numel(), stream)
     assert rc == 0
     ty = torch.matmul(ta, two.t())
     tout = B.aeris_gate_residual_fwd(tx, ty, talpha, rps)
@@ -110,8 +112,8 @@ def test_attention_half_of_a_layer_forward_and_backward():
     tdqkv = torch.empty_like(tqkv)
     rc = lib.aeris_winattn_rope_bwd(ctypes.byref(p), ctypes.byref(r), part(tqkv, 0), part(tqkv, 1),
                                     part(tqkv, 2), ta.data_ptr(), tlse.data_ptr(), tda.data_ptr(),
-                                    part(tdqkv, 0), part(tdqkv, 1), part(tdqkv, 2), ws.data_ptr(),
-                                    ws.numel(), stream)
+                                    part(tdqkv, 0), part(tdqkv, 1), part(tdqkv, 2), fws.data_ptr(),
+                                    ws.data_ptr(), ws.numel(), stream)
     assert rc == 0
     tdwqkv = torch.matmul(tdqkv.t().float(), th.float())
     tdh = torch.matmul(tdqkv, twqkv)

@@ -79,13 +79,19 @@ def run_rope_case(shape, win, shift, mask, mode, base=100.0, kind="normal", seed
     assert np.linalg.norm(o_plain - o_ref) > 0.05 * np.linalg.norm(o_ref)
     for out in outs:
         bf = out == B.AERIS_DT_BF16
-        o, lse = B.aeris_winattn_rope_fwd(tq, tk, tv, win, shift, base, mode, mask, out_dtype=out)
+        o, lse, saved = B.aeris_winattn_rope_fwd(tq, tk, tv, win, shift, base, mode, mask,
+                                                 out_dtype=out, return_saved=True)
         torch.cuda.synchronize()
         check("o", o, o_ref, bf)
         check_lse(lse, lse_ref)
+        # with the rotated operands the forward call left behind, and rotating again: same bits
         dq, dk, dv = B.aeris_winattn_rope_bwd(tq, tk, tv, o, lse, tdo, win, shift, base, mode, mask,
-                                              out_dtype=out)
+                                              out_dtype=out, saved=saved)
+        again = B.aeris_winattn_rope_bwd(tq, tk, tv, o, lse, tdo, win, shift, base, mode, mask,
+                                         out_dtype=out)
         torch.cuda.synchronize()
+        for a, b in zip((dq, dk, dv), again):
+            assert torch.equal(a, b)
         check("dq", dq, dq_ref, bf)
         check("dk", dk, dk_ref, bf)
         check("dv", dv, dv_ref, bf)
@@ -130,10 +136,10 @@ def test_rope_band_share_full_size_sampled():
     Bn, H, W, nh, d = shape
     base, mode = 100.0, B.AERIS_ROPE_POS_GRID
     tq, tk, tv, tdo = synth.make_inputs_device("blend", 4301, shape, 4)
-    o, lse = B.aeris_winattn_rope_fwd(tq, tk, tv, win, shift, base, mode, mask,
-                                      out_dtype=B.AERIS_DT_F32)
+    o, lse, saved = B.aeris_winattn_rope_fwd(tq, tk, tv, win, shift, base, mode, mask,
+                                             out_dtype=B.AERIS_DT_F32, return_saved=True)
     dq, dk, dv = B.aeris_winattn_rope_bwd(tq, tk, tv, o, lse, tdo, win, shift, base, mode, mask,
-                                          out_dtype=B.AERIS_DT_F32)
+                                          out_dtype=B.AERIS_DT_F32, saved=saved)
     torch.cuda.synchronize()
     phi = ro.angles(H, W, d, win, shift, base, ro.POS_GRID)
 
@@ -196,17 +202,21 @@ def test_rope_attention_on_packed_qkv_is_bitwise_the_contiguous_result():
     lib = B.load()
     ptr = lambda t, i: t.data_ptr() + i * nh * d * 2
     stream = torch.cuda.current_stream().cuda_stream
+    fws = torch.empty(B.aeris_winattn_rope_fwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
     ws = torch.empty(B.aeris_winattn_rope_bwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
     rc = lib.aeris_winattn_rope_fwd(ctypes.byref(p), ctypes.byref(r), ptr(packed, 0), ptr(packed, 1),
-                                    ptr(packed, 2), o.data_ptr(), lse.data_ptr(), ws.data_ptr(),
-                                    ws.numel(), stream)
+                                    ptr(packed, 2), o.data_ptr(), lse.data_ptr(), fws.data_ptr(),
+                                    fws.numel(), stream)
     assert rc == 0
-    rc = lib.aeris_winattn_rope_bwd(ctypes.byref(p), ctypes.byref(r), ptr(packed, 0), ptr(packed, 1),
-                                    ptr(packed, 2), o.data_ptr(), lse.data_ptr(), tdo.data_ptr(),
-                                    ptr(dpacked, 0), ptr(dpacked, 1), ptr(dpacked, 2), ws.data_ptr(),
-                                    ws.numel(), stream)
-    assert rc == 0
-    torch.cuda.synchronize()
-    assert torch.equal(o, o_ref) and torch.equal(lse, lse_ref)
-    for i, ref in enumerate((dq_ref, dk_ref, dv_ref)):
-        assert torch.equal(dpacked[:, :, :, i].contiguous().view(torch.int16), ref.view(torch.int16))
+    for saved in (None, fws.data_ptr()):      # rotating again, then from the forward's workspace
+        dpacked.fill_(float("nan"))
+        rc = lib.aeris_winattn_rope_bwd(ctypes.byref(p), ctypes.byref(r), ptr(packed, 0),
+                                        ptr(packed, 1), ptr(packed, 2), o.data_ptr(), lse.data_ptr(),
+                                        tdo.data_ptr(), ptr(dpacked, 0), ptr(dpacked, 1),
+                                        ptr(dpacked, 2), saved, ws.data_ptr(), ws.numel(), stream)
+        assert rc == 0
+        torch.cuda.synchronize()
+        assert torch.equal(o, o_ref) and torch.equal(lse, lse_ref)
+        for i, ref in enumerate((dq_ref, dk_ref, dv_ref)):
+            assert torch.equal(dpacked[:, :, :, i].contiguous().view(torch.int16),
+                               ref.view(torch.int16))

@@ -99,14 +99,20 @@ def test_rotary_attention_on_a_window_subset(mode):
     lst = torch.tensor(picks, dtype=torch.int32, device="cuda")
     o = torch.full_like(o_ref, float("nan"))
     lse = torch.full_like(lse_ref, float("nan"))
-    B.aeris_winattn_rope_fwd_windows(sq, sk, sv, win, shift, 100.0, mode, lst, o, lse, mask)
-    grads = [torch.full_like(tq, float("nan")) for _ in range(3)]
-    B.aeris_winattn_rope_bwd_windows(sq, sk, sv, o, lse, sdo, win, shift, 100.0, mode, lst, *grads,
-                                     mask=mask)
+    p = B.make_params(shape, win, shift, mask)
+    fws = torch.empty(B.aeris_winattn_rope_fwd_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    fws.fill_(0xFF)                     # bf16 NaN everywhere the forward call does not write
+    B.aeris_winattn_rope_fwd_windows(sq, sk, sv, win, shift, 100.0, mode, lst, o, lse, mask,
+                                     workspace=fws)
     torch.cuda.synchronize()
     assert torch.equal(o[:, inside], o_ref[:, inside])
     assert torch.equal(lse[:, :, inside], lse_ref[:, :, inside])
     assert torch.isnan(o[:, ~inside]).all() and torch.isnan(lse[:, :, ~inside]).all()
-    for g, ref in zip(grads, g_ref):
-        assert torch.equal(g[:, inside], ref[:, inside])
-        assert torch.isnan(g[:, ~inside]).all()
+    for saved in (None, fws):           # rotating the share again, then from the forward's copies
+        grads = [torch.full_like(tq, float("nan")) for _ in range(3)]
+        B.aeris_winattn_rope_bwd_windows(sq, sk, sv, o, lse, sdo, win, shift, 100.0, mode, lst,
+                                         *grads, mask=mask, saved=saved)
+        torch.cuda.synchronize()
+        for g, ref in zip(grads, g_ref):
+            assert torch.equal(g[:, inside], ref[:, inside])
+            assert torch.isnan(g[:, ~inside]).all()
