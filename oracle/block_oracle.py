@@ -25,6 +25,13 @@ the ones of the cited works:
   * SwiGLU gate on the packed up-projection uv = [u | v] (u = first F columns):
         g_f = silu(u_f) v_f,   silu(u) = u / (1 + exp(-u)).
 
+  * the branches' input projections act on the normalised, modulated rows
+    (the paper: RMSNorm precedes the projection of queries, keys and values,
+    and the fully connected part): with a weight W [F, C] (one row per output
+    feature, as a linear layer stores it)
+        y_f = sum_c h_c W_{f,c};
+    the SwiGLU up-projection has 2F' rows, the first F' giving u, the rest v.
+
 Rows are tokens; the sample of row i is i // rows_per_sample.  The backward
 functions are the exact derivatives of these maps (sums over the tokens of a
 sample for gamma, beta, alpha; over all tokens for w).
@@ -125,3 +132,25 @@ def swiglu_bwd(uv, dg):
     sg = _sigmoid(u)
     dsilu = sg * (1.0 + u * (1.0 - sg))                # d silu / d u
     return np.concatenate([dg * v * dsilu, dg * u * sg], axis=1)
+
+
+def linear_fwd(x, weight):
+    """y [N, F] = x [N, C] W^T for W [F, C] (the output projection of a branch)."""
+    x = np.asarray(x, dtype=np.float64)
+    weight = np.asarray(weight, dtype=np.float64)
+    if weight.ndim != 2 or weight.shape[1] != x.shape[1]:
+        raise ValueError("weight must be [out_features, channels]")
+    return x @ weight.T
+
+
+def norm_linear_fwd(x, w, gamma, beta, eps, rows_per_sample, weight):
+    """Projection of the normalised, modulated rows: y = h W^T, h as in rmsnorm_adaln_fwd."""
+    h, _ = rmsnorm_adaln_fwd(x, w, gamma, beta, eps, rows_per_sample)
+    return linear_fwd(h, weight)
+
+
+def norm_linear_swiglu_fwd(x, w, gamma, beta, eps, rows_per_sample, weight):
+    """SwiGLU up-projection of the normalised, modulated rows and its gate:
+    uv = h W^T with W [2F, C] = [u rows ; v rows];  returns (g [N, F], uv [N, 2F])."""
+    uv = norm_linear_fwd(x, w, gamma, beta, eps, rows_per_sample, weight)
+    return swiglu_fwd(uv), uv

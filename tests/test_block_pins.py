@@ -235,3 +235,85 @@ def test_rows_must_be_whole_samples():
         bo.rmsnorm_adaln_fwd(np.ones((5, 4)), np.ones(4), np.zeros((2, 4)), np.zeros((2, 4)), 0.0, 2)
     with pytest.raises(ValueError):
         bo.swiglu_fwd(np.ones((2, 5)))
+
+
+# ---------------------------------------------------------------- projections of the normalised rows
+def test_norm_linear_row_worked_by_hand():
+    # the row of test_rmsnorm_row_worked_by_hand: h = (9/sqrt(12.5) + 1, 2)
+    x = np.array([[3.0, 4.0]])
+    w = np.array([2.0, 0.5])
+    gamma = np.array([[0.5, -1.0]])
+    beta = np.array([[1.0, 2.0]])
+    weight = np.array([[1.0, 0.0], [0.0, 1.0], [2.0, -3.0]])       # [F = 3, C = 2]
+    y = bo.norm_linear_fwd(x, w, gamma, beta, 0.0, 1, weight)
+    h0 = 9.0 / math.sqrt(12.5) + 1.0
+    np.testing.assert_allclose(y, [[h0, 2.0, 2.0 * h0 - 6.0]], rtol=0, atol=1e-14)
+    # SwiGLU on a 4-row weight: u = (y0, y1), v = (y2, y0 + y1)
+    w4 = np.array([[1.0, 0.0], [0.0, 1.0], [2.0, -3.0], [1.0, 1.0]])
+    g, uv = bo.norm_linear_swiglu_fwd(x, w, gamma, beta, 0.0, 1, w4)
+    np.testing.assert_allclose(uv, [[h0, 2.0, 2.0 * h0 - 6.0, h0 + 2.0]], rtol=0, atol=1e-14)
+    silu = lambda t: t / (1.0 + math.exp(-t))
+    np.testing.assert_allclose(g, [[silu(h0) * (2.0 * h0 - 6.0), silu(2.0) * (h0 + 2.0)]],
+                               rtol=0, atol=1e-14)
+
+
+def test_norm_linear_against_scalar_loops_and_torch():
+    rng = np.random.default_rng(31)
+    B, rows, C, F = 2, 3, 6, 4                                    # F != C: a transposed W cannot pass
+    x = _rand(rng, B * rows, C)
+    w, gamma, beta = 1.0 + 0.1 * _rand(rng, C), 0.3 * _rand(rng, B, C), _rand(rng, B, C)
+    weight = _rand(rng, 2 * F, C)
+    eps = 1e-5
+    g, uv = bo.norm_linear_swiglu_fwd(x, w, gamma, beta, eps, rows, weight)
+    # scalar loops, nothing shared with the oracle
+    for i in range(B * rows):
+        b = i // rows
+        ms = sum(x[i, c] ** 2 for c in range(C)) / C
+        r = 1.0 / math.sqrt(ms + eps)
+        h = [x[i, c] * r * w[c] * (1.0 + gamma[b, c]) + beta[b, c] for c in range(C)]
+        for f in range(2 * F):
+            want = sum(h[c] * weight[f, c] for c in range(C))
+            assert uv[i, f] == pytest.approx(want, abs=1e-13)
+        for f in range(F):
+            u, v = uv[i, f], uv[i, F + f]
+            assert g[i, f] == pytest.approx(u / (1.0 + math.exp(-u)) * v, abs=1e-13)
+    np.testing.assert_allclose(bo.norm_linear_fwd(x, w, gamma, beta, eps, rows, weight), uv,
+                               rtol=0, atol=0)
+    # torch's own routines in double
+    tx = torch.tensor(x)
+    n = torch.nn.functional.rms_norm(tx, (C,), weight=torch.tensor(w), eps=eps)
+    bidx = torch.arange(B * rows) // rows
+    th = n * (1.0 + torch.tensor(gamma)[bidx]) + torch.tensor(beta)[bidx]
+    tuv = torch.nn.functional.linear(th, torch.tensor(weight))
+    np.testing.assert_allclose(uv, tuv.numpy(), rtol=0, atol=1e-13)
+    tg = torch.nn.functional.silu(tuv[:, :F]) * tuv[:, F:]
+    np.testing.assert_allclose(g, tg.numpy(), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(bo.linear_fwd(x, weight), x @ weight.T, rtol=0, atol=0)
+    with pytest.raises(ValueError):
+        bo.linear_fwd(x, weight.T)
+
+
+def test_norm_linear_invariants():
+    rng = np.random.default_rng(32)
+    B, rows, C, F = 2, 4, 8, 5
+    x = _rand(rng, B * rows, C)
+    w, gamma, beta = _rand(rng, C), 0.2 * _rand(rng, B, C), _rand(rng, B, C)
+    weight = _rand(rng, F, C)
+    y = bo.norm_linear_fwd(x, w, gamma, beta, 0.0, rows, weight)
+    # without eps the projection does not see the scale of a row
+    np.testing.assert_allclose(bo.norm_linear_fwd(3.0 * x, w, gamma, beta, 0.0, rows, weight), y,
+                               rtol=1e-12)
+    # zero rows leave the shift alone: y = beta_b W^T
+    y0 = bo.norm_linear_fwd(np.zeros_like(x), w, gamma, beta, 1e-6, rows, weight)
+    np.testing.assert_allclose(y0[:rows], np.tile(beta[0] @ weight.T, (rows, 1)), rtol=1e-13)
+    np.testing.assert_allclose(y0[rows:], np.tile(beta[1] @ weight.T, (rows, 1)), rtol=1e-13)
+    # linear in W; and the folded form the kernels use is the same map:
+    #   y_i = r_i * x_i (W diag(w (1 + gamma_b)))^T + beta_b W^T
+    np.testing.assert_allclose(bo.norm_linear_fwd(x, w, gamma, beta, 0.0, rows, 2.0 * weight), 2.0 * y,
+                               rtol=1e-13)
+    _, r = bo.rmsnorm_adaln_fwd(x, w, gamma, beta, 0.0, rows)
+    for b in range(B):
+        sl = slice(b * rows, (b + 1) * rows)
+        folded = weight * (w * (1.0 + gamma[b]))[None, :]
+        np.testing.assert_allclose(r[sl, None] * (x[sl] @ folded.T) + beta[b] @ weight.T, y[sl],
+                                   rtol=0, atol=1e-12)
