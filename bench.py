@@ -120,9 +120,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS) + ["layer_ops"],
+    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS) + ["layer_ops", "qkv_proj"],
                     help="layer_ops: the element-wise kernels of include/aeris_layer_ops.h on the "
-                         "headline grid's tokens (a bandwidth figure, not the headline metric)")
+                         "headline grid's tokens (a bandwidth figure, not the headline metric); "
+                         "qkv_proj: the fused RMSNorm + modulation + QKV projection and the fused "
+                         "SwiGLU up-projection on the same tokens (bf16 MFMA TFLOP/s)")
     ap.add_argument("--channels", type=int, default=2048, help="row width for --workload layer_ops")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-pairs", type=int, default=64)
@@ -146,6 +148,8 @@ def main():
     B.load()   # fails loudly if the HIP library is not built
     if args.workload == "layer_ops":
         return bench_layer_ops(args)
+    if args.workload == "qkv_proj":
+        return bench_projections(args)
     wl = WORKLOADS[args.workload]
     shape, win, mask = wl["shape"], wl["win"], wl["mask"]
     Bn, H, W, nh, d = shape
@@ -378,6 +382,82 @@ def cpu_baseline(wl, tq, tk, tv, tdo, n_pairs):
             "sample": "%d (batch, window, head) pairs of the workload (interior, seam and corner "
                       "windows), fwd%s, %.1f s of CPU time" %
                       (n_pairs, "+bwd" if tdo is not None else "", secs)}
+
+
+def bench_projections(args):
+    """One step = the fused QKV projection (2048 -> 6144) and the fused SwiGLU up-projection
+    (2048 -> 2 x 5504, gate in the epilogue) of one layer on 4 x 720 x 1440 token rows.  FLOPs =
+    2 * rows * channels * features per GEMM; torch's bf16 matmul (the vendor GEMM) on the same
+    shape is timed beside them as context."""
+    import numpy as np
+    import torch
+    from paper_2509_13523_amd import binding as B
+    nb, rps, C = 4, 720 * 1440, args.channels
+    n, F, hidden = nb * rps, 3 * args.channels, 5504
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    gen = torch.Generator(device=dev).manual_seed(7100)
+    x = torch.randn(n, C, device=dev, dtype=torch.bfloat16, generator=gen)
+    wqkv = (torch.randn(F, C, device=dev, generator=gen) / C ** 0.5).to(torch.bfloat16)
+    wup = (torch.randn(2 * hidden, C, device=dev, generator=gen) / C ** 0.5).to(torch.bfloat16)
+    w = 1.0 + 0.1 * torch.randn(C, device=dev, generator=gen)
+    gamma = 0.3 * torch.randn(nb, C, device=dev, generator=gen)
+    beta = 0.5 * torch.randn(nb, C, device=dev, generator=gen)
+    y = torch.empty(n, F, dtype=torch.bfloat16, device=dev)
+    g = torch.empty(n, hidden, dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(B.aeris_norm_linear_workspace_bytes(n, rps, C, 2 * hidden), dtype=torch.uint8,
+                     device=dev)
+    ops = [("norm_qkv_projection", lambda: B.aeris_norm_linear_fwd(x, w, gamma, beta, 1e-6, wqkv, rps,
+                                                                  y=y, workspace=ws), 2.0 * n * C * F),
+           ("norm_swiglu_up_projection", lambda: B.aeris_norm_linear_swiglu_fwd(
+               x, w, gamma, beta, 1e-6, wup, rps, g=g, want_uv=False, workspace=ws),
+            2.0 * n * C * 2 * hidden)]
+    for _ in range(args.warmup):
+        for _, fn, _ in ops:
+            fn()
+    torch.cuda.synchronize()
+    ev = {name: [] for name, _, _ in ops}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        for name, fn, _ in ops:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            ev[name].append((e0, e1))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    step_ms = wall * 1e3 / args.steps
+    per = {}
+    for name, _, fl in ops:
+        ts = sorted(a.elapsed_time(b) for a, b in ev[name])
+        per[name] = {"median_ms": round(ts[len(ts) // 2], 3), "min_ms": round(ts[0], 3),
+                     "tflops": round(fl / (ts[len(ts) // 2] * 1e-3) / 1e12, 1)}
+    # context: the vendor GEMM on the QKV shape (no normalisation, no epilogue)
+    torch.matmul(x, wqkv.t(), out=y)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(3):
+        torch.matmul(x, wqkv.t(), out=y)
+    e1.record()
+    torch.cuda.synchronize()
+    vendor_ms = e0.elapsed_time(e1) / 3
+    total = sum(fl for _, _, fl in ops)
+    slow = max(ops, key=lambda o: per[o[0]]["median_ms"])
+    achieved = per[slow[0]]["tflops"]
+    print(json.dumps({
+        "metric": "fused_projection_tflops", "value": round(total / (step_ms * 1e-3) / 1e12, 1),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "qkv_proj: %d x %d token rows, %d channels -> %d (QKV) and 2 x %d "
+                               "(SwiGLU up, gated)" % (nb, rps, C, F, hidden), "kernels": per,
+                   "vendor_gemm_qkv_shape_ms": round(vendor_ms, 3),
+                   "vendor_gemm_qkv_shape_tflops": round(2.0 * n * C * F / (vendor_ms * 1e-3) / 1e12, 1)},
+        "roofline": {"kernel": "norm_linear_gemm_kernel (%s)" % slow[0], "bound": "mfma",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None}}))
 
 
 def bench_layer_ops(args):

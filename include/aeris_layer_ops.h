@@ -5,9 +5,10 @@
  * The AERIS paper ("AERIS Model Architecture") builds every layer from a pre-RMSNorm (in place
  * of LayerNorm), an attention or SwiGLU branch, and adaptive-layer-norm values alpha, beta,
  * gamma that a layer-specific linear map derives from the diffusion-time embedding.  It prints
- * no formulas; the ones below are those of the works it cites for each part.  The matrix
- * products of a layer (QKV, output and SwiGLU projections) are plain GEMMs and are NOT part of
- * this library.
+ * no formulas; the ones below are those of the works it cites for each part.  The input
+ * projections of the two branches (QKV, SwiGLU up-projection) are offered with the RMSNorm and
+ * the modulation folded in (last section of this file), the output projections as a plain
+ * bf16 product; the backward products of the projections are plain GEMMs left to the caller.
  *
  * Rows are tokens.  Activations are bf16, row-major [n_rows, channels], rows contiguous
  * (stride = channels).  The sample of row i is i / rows_per_sample: the tokens of one sample
@@ -98,6 +99,49 @@ int aeris_swiglu_fwd(const void* uv, int64_t n_rows, int32_t hidden, void* g, vo
  */
 int aeris_swiglu_bwd(const void* uv, const void* dg, int64_t n_rows, int32_t hidden, void* duv,
                      void* hip_stream);
+
+/*
+ * Input projections with the pre-RMSNorm and the modulation folded in (Model Architecture:
+ * RMSNorm and the adaptive-layer-norm values precede the projection of queries, keys and values
+ * and the SwiGLU feed-forward part).  With h as in aeris_rmsnorm_adaln_fwd and a weight
+ * `weight` [out_features, channels] bf16 (one row per output feature, rows contiguous):
+ *     y [n_rows, out_features] = h weight^T          (bf16)
+ * h is never written.  The call computes r by a row pass over x, folds w (1 + gamma_b) into a
+ * per-sample copy of the weight (rounded to bf16: the products multiply in bf16) and beta_b
+ * into a per-sample bias beta_b weight^T (fp32), and runs one bf16 GEMM on the raw rows x whose
+ * epilogue applies r and the bias:  y_i = r_i x_i Wf_b^T + bias_b.
+ * For QKV, weight = [Wq ; Wk ; Wv] gives y = [B, H, W, 3, heads, head_dim], the packed layout
+ * the attention entry points take through their stride fields.
+ * Limits: channels % 64 == 0, 64 <= channels <= AERIS_MAX_PROJECTION_CHANNELS,
+ * out_features % 8 == 0, out_features * channels < 2^31.  workspace: >=
+ * aeris_norm_linear_workspace_bytes(...) bytes (folded weights, biases, r), 16-byte aligned,
+ * contents undefined before and after.
+ */
+#define AERIS_MAX_PROJECTION_CHANNELS 8192
+size_t aeris_norm_linear_workspace_bytes(int64_t n_rows, int64_t rows_per_sample,
+                                         int32_t channels, int32_t out_features);
+int aeris_norm_linear_fwd(const void* x, const float* w, const float* gamma, const float* beta,
+                          float eps, const void* weight, int64_t n_rows, int64_t rows_per_sample,
+                          int32_t channels, int32_t out_features, void* y, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The SwiGLU up-projection the same way, with the gate as a second epilogue: weight
+ * [2*hidden, channels] = [u rows ; v rows],  uv = h weight^T,  g = silu(u) v  [n_rows, hidden]
+ * bf16, formed from the fp32 accumulators.  uv [n_rows, 2*hidden] bf16 is also written if the
+ * pointer is not NULL (aeris_swiglu_bwd needs it).  workspace as above with
+ * out_features = 2*hidden.
+ */
+int aeris_norm_linear_swiglu_fwd(const void* x, const float* w, const float* gamma,
+                                 const float* beta, float eps, const void* weight, int64_t n_rows,
+                                 int64_t rows_per_sample, int32_t channels, int32_t hidden,
+                                 void* g, void* uv, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream);
+
+/* Output projection of a branch: y [n_rows, out_features] = x weight^T, bf16 in and out, fp32
+ * accumulation, same kernel without the folded parts.  Limits as above. */
+int aeris_linear_fwd(const void* x, const void* weight, int64_t n_rows, int32_t channels,
+                     int32_t out_features, void* y, void* hip_stream);
 
 #ifdef __cplusplus
 }

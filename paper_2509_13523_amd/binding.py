@@ -28,7 +28,8 @@ EXPORTS = ("aeris_winattn_fwd", "aeris_winattn_bwd", "aeris_winattn_bwd_stages",
            "aeris_rmsnorm_adaln_fwd", "aeris_rmsnorm_adaln_bwd_workspace_bytes",
            "aeris_rmsnorm_adaln_bwd", "aeris_gate_residual_fwd",
            "aeris_gate_residual_bwd_workspace_bytes", "aeris_gate_residual_bwd",
-           "aeris_swiglu_fwd", "aeris_swiglu_bwd")
+           "aeris_swiglu_fwd", "aeris_swiglu_bwd", "aeris_norm_linear_workspace_bytes",
+           "aeris_norm_linear_fwd", "aeris_norm_linear_swiglu_fwd", "aeris_linear_fwd")
 
 
 class aeris_winattn_params(ctypes.Structure):
@@ -128,6 +129,15 @@ def load():
     lib.aeris_swiglu_fwd.restype = ctypes.c_int
     lib.aeris_swiglu_bwd.argtypes = [vp, vp, i64, i32, vp, vp]
     lib.aeris_swiglu_bwd.restype = ctypes.c_int
+    lib.aeris_norm_linear_workspace_bytes.argtypes = [i64, i64, i32, i32]
+    lib.aeris_norm_linear_workspace_bytes.restype = sz
+    lib.aeris_norm_linear_fwd.argtypes = [vp, vp, vp, vp, f32, vp, i64, i64, i32, i32, vp, vp, sz, vp]
+    lib.aeris_norm_linear_fwd.restype = ctypes.c_int
+    lib.aeris_norm_linear_swiglu_fwd.argtypes = [vp, vp, vp, vp, f32, vp, i64, i64, i32, i32, vp, vp,
+                                                 vp, sz, vp]
+    lib.aeris_norm_linear_swiglu_fwd.restype = ctypes.c_int
+    lib.aeris_linear_fwd.argtypes = [vp, vp, i64, i32, i32, vp, vp]
+    lib.aeris_linear_fwd.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -553,3 +563,77 @@ def aeris_swiglu_bwd(uv, dg, duv=None):
     if rc != 0:
         raise AerisError(rc, "aeris_swiglu_bwd")
     return duv
+
+
+def aeris_norm_linear_workspace_bytes(n_rows, rows_per_sample, channels, out_features):
+    return load().aeris_norm_linear_workspace_bytes(n_rows, rows_per_sample, channels, out_features)
+
+
+def _check_projection(x, w, gamma, beta, weight):
+    import torch
+    n, c = _rows(x)
+    assert weight.is_cuda and weight.dtype == torch.bfloat16 and weight.is_contiguous()
+    assert weight.dim() == 2 and weight.shape[1] == c
+    for t in (w, gamma, beta):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+    return n, c
+
+
+def aeris_norm_linear_fwd(x, w, gamma, beta, eps, weight, rows_per_sample, y=None, workspace=None):
+    """y = (RMSNorm(x; w) (1 + gamma_b) + beta_b) weight^T without writing the normalised rows.
+    x [N, C] bf16, weight [F, C] bf16; returns y [N, F] bf16."""
+    import torch
+    n, c = _check_projection(x, w, gamma, beta, weight)
+    f = weight.shape[0]
+    if y is None:
+        y = torch.empty((n, f), dtype=torch.bfloat16, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(aeris_norm_linear_workspace_bytes(n, rows_per_sample, c, f),
+                                dtype=torch.uint8, device=x.device)
+    rc = load().aeris_norm_linear_fwd(x.data_ptr(), w.data_ptr(), gamma.data_ptr(), beta.data_ptr(),
+                                      float(eps), weight.data_ptr(), n, rows_per_sample, c, f,
+                                      y.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                      _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_norm_linear_fwd")
+    return y
+
+
+def aeris_norm_linear_swiglu_fwd(x, w, gamma, beta, eps, weight, rows_per_sample, g=None, uv=None,
+                                 want_uv=True, workspace=None):
+    """SwiGLU up-projection of the normalised rows with the gate in the epilogue.
+    weight [2*hidden, C] = [u rows ; v rows]; returns (g [N, hidden], uv [N, 2*hidden] or None)."""
+    import torch
+    n, c = _check_projection(x, w, gamma, beta, weight)
+    f2 = weight.shape[0]
+    assert f2 % 2 == 0
+    if g is None:
+        g = torch.empty((n, f2 // 2), dtype=torch.bfloat16, device=x.device)
+    if uv is None and want_uv:
+        uv = torch.empty((n, f2), dtype=torch.bfloat16, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(aeris_norm_linear_workspace_bytes(n, rows_per_sample, c, f2),
+                                dtype=torch.uint8, device=x.device)
+    rc = load().aeris_norm_linear_swiglu_fwd(x.data_ptr(), w.data_ptr(), gamma.data_ptr(),
+                                             beta.data_ptr(), float(eps), weight.data_ptr(), n,
+                                             rows_per_sample, c, f2 // 2, g.data_ptr(),
+                                             None if uv is None else uv.data_ptr(),
+                                             workspace.data_ptr(), workspace.numel(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_norm_linear_swiglu_fwd")
+    return g, uv
+
+
+def aeris_linear_fwd(x, weight, y=None):
+    """y = x weight^T (bf16 in and out, fp32 accumulation)."""
+    import torch
+    n, c = _rows(x)
+    assert weight.is_cuda and weight.dtype == torch.bfloat16 and weight.is_contiguous()
+    assert weight.dim() == 2 and weight.shape[1] == c
+    if y is None:
+        y = torch.empty((n, weight.shape[0]), dtype=torch.bfloat16, device=x.device)
+    rc = load().aeris_linear_fwd(x.data_ptr(), weight.data_ptr(), n, c, weight.shape[0],
+                                 y.data_ptr(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_linear_fwd")
+    return y

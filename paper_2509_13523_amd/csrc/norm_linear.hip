@@ -1,0 +1,421 @@
+// Input projections of an AERIS transformer layer with the pre-RMSNorm and the adaptive
+// modulation folded in (paper, Model Architecture section: RMSNorm and the adaptive-layer-norm
+// values precede the projection of queries, keys and values and the SwiGLU feed-forward part);
+// argument contracts in include/aeris_layer_ops.h.
+//
+// The normalised, modulated row h_c = x_c r w_c (1 + gamma_bc) + beta_bc is never written:
+//     y_f = sum_c h_c W_fc = r * sum_c x_c (W_fc w_c (1 + gamma_bc)) + sum_c beta_bc W_fc,
+// so the projection is a plain bf16 GEMM of the raw rows x with a per-sample folded weight
+//     Wf_b = W diag(w (1 + gamma_b))        (bf16, built by a small kernel per call)
+// followed, in the epilogue, by the row's reciprocal RMS r (from a row pass over x) and a
+// per-sample bias beta_b W^T.  The SwiGLU gate is a second epilogue: a workgroup's tile holds
+// matching u and v columns, so g = silu(u) v is formed on the accumulators.
+//
+// GEMM kernel: one workgroup of eight wavefronts per 256 x 256 output tile, 64 channels per
+// step, both operands K-contiguous ("NT").  Operand tiles go global -> LDS directly
+// (global_load_lds_dwordx4), two stages of 64 KB, 16-byte chunks XOR-swizzled so that the
+// row-major ds_read_b128 operand fetches are conflict free; v_mfma_f32_32x32x16_bf16 with the
+// weight rows as the A operand and the token rows as the B operand, so that a lane owns one
+// token row of the output: the row scale is a per-lane scalar and a lane's 16 accumulator
+// values are four runs of four consecutive output features (8-byte stores).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "aeris_layer_ops.h"
+#include "aeris_winattn.h"
+#include "winattn_common.hpp"
+#include "winattn_launch.hpp"
+
+namespace aeris {
+namespace {
+
+constexpr int kBM = 256;                 // token rows per workgroup tile
+constexpr int kBN = 256;                 // weight rows (output features) per workgroup tile
+constexpr int kBK = 64;                  // channels per step
+constexpr int kGemmWaves = 8;
+constexpr int kPartBytes = kBN * kBK * 2;            // 32 KB: weight rows, then token rows
+constexpr int kStageBytes = 2 * kPartBytes;
+using Sub = Tile<64, kGemmWaves>;        // 64 rows x 64 channels, swizzled chunks
+
+struct GemmParams {
+  const bf16_t* x;             // [n_rows, K]
+  const bf16_t* w;             // [F, K], or per sample [n_samples][F, K]
+  long long w_sample_stride;   // elements between the samples' matrices (0: one for all)
+  const float* r;              // [n_rows] row scale, or null
+  const float* bias;           // [n_samples][F], or null
+  bf16_t* y;                   // [n_rows, F]: the projection (plain), or uv (SwiGLU, may be null)
+  bf16_t* g;                   // SwiGLU: [n_rows, F / 2]
+  long long rows_per_sample;
+  int m_tiles_per_sample;
+  int m_tiles;                 // n_samples * m_tiles_per_sample
+  int n_tiles;
+  int K, F;
+  int swiglu;
+};
+
+// Workgroup id -> (token tile, feature tile).  Consecutive ids go to the eight XCDs in turn;
+// the 32 workgroups an XCD runs at a time are 8 token tiles x 4 feature tiles, so every
+// operand tile that arrives in that XCD's L2 serves 4 or 8 workgroups.
+__device__ __forceinline__ bool gemm_tile(const GemmParams& p, int& mt, int& nt) {
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int per_group = 8 * p.n_tiles;
+  const int group = slot / per_group, rem = slot - group * per_group;
+  nt = rem >> 3;
+  mt = ((group * 8 + (rem & 7)) << 3) + xcd;
+  return mt < p.m_tiles;
+}
+inline unsigned gemm_grid(const GemmParams& p) {
+  return 8u * (unsigned)((p.m_tiles + 63) / 64) * 8u * (unsigned)p.n_tiles;
+}
+
+__device__ __forceinline__ float silu(float u) {
+  return u * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-u * kLog2e));
+}
+
+__global__ __launch_bounds__(kGemmWaves * 64, 1) void norm_linear_gemm_kernel(GemmParams p) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  int mt, nt;
+  if (!gemm_tile(p, mt, nt)) return;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2, wn = wave & 3;          // 2 x 4 waves: 128 token rows x 64 features
+  const int li = lane & 31, g = lane >> 5;
+
+  const int sample = mt / p.m_tiles_per_sample;
+  const int tile_in_sample = mt - sample * p.m_tiles_per_sample;
+  const long long row0 = (long long)sample * p.rows_per_sample + (long long)tile_in_sample * kBM;
+  const long long rows_left = p.rows_per_sample - (long long)tile_in_sample * kBM;
+  const int valid_rows = rows_left < kBM ? (int)rows_left : kBM;
+  const int hidden = p.F >> 1;
+
+  // Feature (weight row) of tile row R.  SwiGLU tiles pair 128 u-features with their
+  // v-features: wave column wn holds u rows in its first 32 tile rows, v rows in the next 32.
+  auto feature = [&](int R) __attribute__((always_inline)) {
+    if (p.swiglu) {
+      int j = nt * (kBN / 2) + (R >> 6) * 32 + (R & 31);
+      j = j < hidden ? j : hidden - 1;
+      return ((R >> 5) & 1) ? hidden + j : j;
+    }
+    const int f = nt * kBN + R;
+    return f < p.F ? f : p.F - 1;
+  };
+
+  // ---- copies: instruction j (0..63) moves rows 8j..8j+7 of the stage; wave w issues
+  // j = w + 8i.  i < 4: weight rows, i >= 4: token rows.  Rows past the end repeat the last
+  // valid row (never stored).  Lane: row j*8 + lane/8, LDS chunk position lane%8.
+  const bf16_t* wmat = p.w + (long long)sample * p.w_sample_stride;
+  const unsigned long long wbase = reinterpret_cast<unsigned long long>(wmat);
+  const unsigned long long xbase = reinterpret_cast<unsigned long long>(p.x + row0 * p.K);
+  uint32_t voff[8];
+  {
+    const int r_in = lane >> 3;
+    const int r_sub = ((wave & 1) << 3) | r_in;                  // row within a 64-row sub-tile, mod 16
+    const int chunk = (lane & 7) ^ Sub::swz(r_sub);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int R = ((wave + 8 * i) << 3) + r_in;               // 0..511
+      if (i < 4) {
+        voff[i] = (uint32_t)((long long)feature(R) * p.K * 2 + chunk * 16);
+      } else {
+        int m = R - kBN;
+        m = m < valid_rows ? m : valid_rows - 1;
+        voff[i] = (uint32_t)((long long)m * p.K * 2 + chunk * 16);
+      }
+    }
+  }
+  const uint32_t lds0 = lds_address(smem);
+  auto copy_piece = [&](int i, uint32_t stage, int k0, uint32_t enable) __attribute__((always_inline)) {
+    async_copy16_off(voff[i], (i < 4 ? wbase : xbase) + (unsigned long long)k0 * 2,
+                     stage + (uint32_t)((wave + 8 * i) << 10), enable);
+  };
+
+  // ---- operand reads: per lane four chunk offsets (one per 16-channel block of a step)
+  uint32_t va[4], vb[4];
+  {
+    const int s = Sub::swz(li);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const uint32_t off = li * 128 + (((2 * kk + g) ^ s) << 4);
+      va[kk] = lds0 + wn * 8192 + off;
+      vb[kk] = lds0 + kPartBytes + wm * 16384 + off;
+    }
+  }
+
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+  const int k_steps = p.K / kBK;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) copy_piece(i, lds0, 0, 1);
+
+  bf16x8 ao[2][2], bo[2][4];
+  auto fetch = [&](int set, int kk, uint32_t stage_off) __attribute__((always_inline)) {
+#pragma unroll
+    for (int a = 0; a < 2; ++a) ao[set][a] = Sub::read_rm(va[kk] + stage_off + a * 4096);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) bo[set][b] = Sub::read_rm(vb[kk] + stage_off + b * 4096);
+  };
+
+  for (int ks = 0; ks < k_steps; ++ks) {
+    const uint32_t stage_off = (ks & 1) * kStageBytes;
+    wait_async_loads();
+    __syncthreads();               // this stage has landed; every reader of the other one is done
+    const uint32_t more = ks + 1 < k_steps;
+    const uint32_t next_stage = lds0 + (kStageBytes - stage_off);
+    fetch(0, 0, stage_off);
+    sched_fence();
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      if (kk < 3) fetch((kk + 1) & 1, kk + 1, stage_off);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          acc[a][b] = mfma32(ao[kk & 1][a], bo[kk & 1][b], acc[a][b]);
+          // the next stage's copies, one per four products
+          if (b == 3) copy_piece(2 * kk + a, next_stage, (ks + 1) * kBK, more);
+        }
+      sched_fence();
+    }
+  }
+
+  // ---- epilogue: row scale, bias, (gate,) 8-byte stores of four consecutive features ------
+  const float* bias = p.bias ? p.bias + (long long)sample * p.F : nullptr;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const int m = wm * 128 + b * 32 + li;
+    if (m >= valid_rows) continue;
+    const long long row = row0 + m;
+    const float rs = p.r ? p.r[row] : 1.f;
+    if (p.swiglu) {
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) {
+        const int j = nt * (kBN / 2) + wn * 32 + 8 * vq + 4 * g;
+        if (j >= hidden) continue;
+        float u[4], v[4];
+        f32x4 bu = {0.f, 0.f, 0.f, 0.f}, bv = bu;
+        if (bias) {
+          bu = *reinterpret_cast<const f32x4*>(bias + j);
+          bv = *reinterpret_cast<const f32x4*>(bias + hidden + j);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          u[e] = __builtin_fmaf(acc[0][b][4 * vq + e], rs, bu[e]);
+          v[e] = __builtin_fmaf(acc[1][b][4 * vq + e], rs, bv[e]);
+        }
+        if (p.y) {
+          store4(p.y + row * p.F + j, u[0], u[1], u[2], u[3]);
+          store4(p.y + row * p.F + hidden + j, v[0], v[1], v[2], v[3]);
+        }
+        store4(p.g + row * hidden + j, silu(u[0]) * v[0], silu(u[1]) * v[1], silu(u[2]) * v[2],
+               silu(u[3]) * v[3]);
+      }
+    } else {
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          const int f = nt * kBN + wn * 64 + a * 32 + 8 * vq + 4 * g;
+          if (f >= p.F) continue;
+          float o[4];
+          f32x4 b4 = {0.f, 0.f, 0.f, 0.f};
+          if (bias) b4 = *reinterpret_cast<const f32x4*>(bias + f);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = __builtin_fmaf(acc[a][b][4 * vq + e], rs, b4[e]);
+          store4(p.y + row * p.F + f, o[0], o[1], o[2], o[3]);
+        }
+    }
+  }
+}
+
+// r_i = (mean_c x_ic^2 + eps)^(-1/2): one wavefront per row, 16 bytes per lane and access.
+__global__ __launch_bounds__(256) void rms_rows_kernel(const bf16_t* __restrict__ x, long long n_rows,
+                                                       int channels, float eps, float* __restrict__ r) {
+  const int lane = threadIdx.x & 63;
+  const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const long long n_waves = (long long)gridDim.x * 4;
+  for (long long row = wave; row < n_rows; row += n_waves) {
+    const bf16_t* xr = x + row * channels;
+    float s = 0.f;
+    for (int c = lane * 8; c < channels; c += 512) {
+      const bf16x8 v = *reinterpret_cast<const bf16x8*>(xr + c);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s = __builtin_fmaf((float)v[e], (float)v[e], s);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d);
+    if (lane == 0) r[row] = 1.f / sqrtf(s / (float)channels + eps);
+  }
+}
+
+// Wf_b[f][c] = bf16(W[f][c] w[c] (1 + gamma_b[c])),  bias_b[f] = sum_c beta_b[c] W[f][c].
+// One workgroup per (feature, sample); the bias sum is taken in a fixed order.
+__global__ __launch_bounds__(256) void fold_weights_kernel(const bf16_t* __restrict__ w_in,
+                                                           const float* __restrict__ w,
+                                                           const float* __restrict__ gamma,
+                                                           const float* __restrict__ beta, int K,
+                                                           int F, bf16_t* __restrict__ w_out,
+                                                           float* __restrict__ bias) {
+  __shared__ float part[4];
+  const int f = blockIdx.x, b = blockIdx.y;
+  const bf16_t* src = w_in + (long long)f * K;
+  bf16_t* dst = w_out + ((long long)b * F + f) * K;
+  float s = 0.f;
+  for (int c = threadIdx.x * 8; c < K; c += 256 * 8) {
+    const bf16x8 v = *reinterpret_cast<const bf16x8*>(src + c);
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float wv = (float)v[e];
+      o[e] = (bf16_t)(wv * (w[c + e] * (1.f + gamma[(long long)b * K + c + e])));
+      s = __builtin_fmaf(beta[(long long)b * K + c + e], wv, s);
+    }
+    *reinterpret_cast<bf16x8*>(dst + c) = o;
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) bias[(long long)b * F + f] = (part[0] + part[1]) + (part[2] + part[3]);
+}
+
+size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+int check_projection(int64_t n_rows, int64_t rows_per_sample, int32_t channels, int32_t features) {
+  if (n_rows <= 0 || rows_per_sample <= 0 || channels <= 0 || features <= 0)
+    return AERIS_ERR_INVALID_SHAPE;
+  if (channels < kBK || channels > AERIS_MAX_PROJECTION_CHANNELS || features < 8)
+    return AERIS_ERR_INVALID_SHAPE;
+  if (channels % kBK != 0 || features % 8 != 0 || n_rows % rows_per_sample != 0)
+    return AERIS_ERR_NOT_DIVISIBLE;
+  if (n_rows / rows_per_sample > 65535) return AERIS_ERR_INVALID_SHAPE;   // a grid dimension
+  // 32-bit byte offsets inside a workgroup's operand tiles, 31-bit tile counts
+  if ((long long)features * channels * 2 >= (1LL << 32)) return AERIS_ERR_INVALID_SHAPE;
+  const long long m_tiles = (n_rows / rows_per_sample) * ((rows_per_sample + kBM - 1) / kBM);
+  const long long n_tiles = (features + kBN - 1) / kBN;
+  if (((m_tiles + 63) / 64) * 64 * n_tiles >= (1LL << 31)) return AERIS_ERR_INVALID_SHAPE;
+  return AERIS_OK;
+}
+
+bool bad16(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15) != 0; }
+
+int launch_gemm(GemmParams p, hipStream_t stream) {
+  p.m_tiles_per_sample = (int)((p.rows_per_sample + kBM - 1) / kBM);
+  if (!allow_full_lds<norm_linear_gemm_kernel>()) return -1;
+  return launch_kernel(norm_linear_gemm_kernel, dim3(gemm_grid(p)), dim3(kGemmWaves * 64),
+                       2 * kStageBytes, stream, p);
+}
+
+struct Folded {
+  bf16_t* w;
+  float* bias;
+  float* r;
+};
+Folded carve(void* workspace, int64_t n_rows, int64_t n_samples, int32_t channels, int32_t features) {
+  char* ws = static_cast<char*>(workspace);
+  Folded f;
+  f.w = reinterpret_cast<bf16_t*>(ws);
+  ws += round256((size_t)n_samples * features * channels * 2);
+  f.bias = reinterpret_cast<float*>(ws);
+  ws += round256((size_t)n_samples * features * 4);
+  f.r = reinterpret_cast<float*>(ws);
+  return f;
+}
+
+// Row pass + weight folding + GEMM.  features = rows of `weight`; swiglu: features = 2 * hidden.
+int norm_projection(const void* x, const float* w, const float* gamma, const float* beta, float eps,
+                    const void* weight, int64_t n_rows, int64_t rows_per_sample, int32_t channels,
+                    int32_t features, bool swiglu, void* y, void* g, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+  if (!x || !w || !gamma || !beta || !weight || !workspace || (!swiglu && !y) || (swiglu && !g))
+    return AERIS_ERR_NULL_POINTER;
+  if (const int rc = check_projection(n_rows, rows_per_sample, channels, features)) return rc;
+  if (!(eps >= 0.f)) return AERIS_ERR_INVALID_SHAPE;
+  if (bad16(x) || bad16(weight) || bad16(y) || bad16(g) || bad16(workspace) || bad16(w) ||
+      bad16(gamma) || bad16(beta))
+    return AERIS_ERR_MISALIGNED;
+  if (workspace_bytes < aeris_norm_linear_workspace_bytes(n_rows, rows_per_sample, channels, features))
+    return AERIS_ERR_WORKSPACE_TOO_SMALL;
+  const hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int64_t n_samples = n_rows / rows_per_sample;
+  const Folded f = carve(workspace, n_rows, n_samples, channels, features);
+  const long long row_blocks = (n_rows + 3) / 4;
+  if (launch_kernel(rms_rows_kernel, dim3((unsigned)(row_blocks < 8192 ? row_blocks : 8192)),
+                    dim3(256), 0, st, static_cast<const bf16_t*>(x), (long long)n_rows, channels,
+                    eps, f.r) != 0 ||
+      launch_kernel(fold_weights_kernel, dim3((unsigned)features, (unsigned)n_samples), dim3(256), 0,
+                    st, static_cast<const bf16_t*>(weight), w, gamma, beta, channels, features,
+                    f.w, f.bias) != 0)
+    return AERIS_ERR_HIP_LAUNCH;
+  GemmParams p{};
+  p.x = static_cast<const bf16_t*>(x);
+  p.w = f.w;
+  p.w_sample_stride = (long long)features * channels;
+  p.r = f.r;
+  p.bias = f.bias;
+  p.y = static_cast<bf16_t*>(y);
+  p.g = static_cast<bf16_t*>(g);
+  p.rows_per_sample = rows_per_sample;
+  p.m_tiles = (int)(n_samples * ((rows_per_sample + kBM - 1) / kBM));
+  p.K = channels;
+  p.F = features;
+  p.swiglu = swiglu ? 1 : 0;
+  p.n_tiles = swiglu ? (features / 2 + kBN / 2 - 1) / (kBN / 2) : (features + kBN - 1) / kBN;
+  return launch_gemm(p, st) == 0 ? AERIS_OK : AERIS_ERR_HIP_LAUNCH;
+}
+
+}  // namespace
+}  // namespace aeris
+
+using namespace aeris;
+
+extern "C" size_t aeris_norm_linear_workspace_bytes(int64_t n_rows, int64_t rows_per_sample,
+                                                    int32_t channels, int32_t out_features) {
+  if (check_projection(n_rows, rows_per_sample, channels, out_features) != AERIS_OK) return 0;
+  const size_t n_samples = (size_t)(n_rows / rows_per_sample);
+  return round256(n_samples * out_features * channels * 2) + round256(n_samples * out_features * 4) +
+         round256((size_t)n_rows * 4);
+}
+
+extern "C" int aeris_norm_linear_fwd(const void* x, const float* w, const float* gamma,
+                                     const float* beta, float eps, const void* weight,
+                                     int64_t n_rows, int64_t rows_per_sample, int32_t channels,
+                                     int32_t out_features, void* y, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream) {
+  return norm_projection(x, w, gamma, beta, eps, weight, n_rows, rows_per_sample, channels,
+                         out_features, false, y, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int aeris_norm_linear_swiglu_fwd(const void* x, const float* w, const float* gamma,
+                                            const float* beta, float eps, const void* weight,
+                                            int64_t n_rows, int64_t rows_per_sample,
+                                            int32_t channels, int32_t hidden, void* g, void* uv,
+                                            void* workspace, size_t workspace_bytes,
+                                            void* hip_stream) {
+  if (hidden <= 0 || hidden > (1 << 29)) return AERIS_ERR_INVALID_SHAPE;
+  if (hidden % 8 != 0) return AERIS_ERR_NOT_DIVISIBLE;
+  return norm_projection(x, w, gamma, beta, eps, weight, n_rows, rows_per_sample, channels,
+                         2 * hidden, true, uv, g, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int aeris_linear_fwd(const void* x, const void* weight, int64_t n_rows, int32_t channels,
+                                int32_t out_features, void* y, void* hip_stream) {
+  if (!x || !weight || !y) return AERIS_ERR_NULL_POINTER;
+  if (const int rc = check_projection(n_rows, n_rows, channels, out_features)) return rc;
+  if (bad16(x) || bad16(weight) || bad16(y)) return AERIS_ERR_MISALIGNED;
+  GemmParams p{};
+  p.x = static_cast<const bf16_t*>(x);
+  p.w = static_cast<const bf16_t*>(weight);
+  p.y = static_cast<bf16_t*>(y);
+  p.rows_per_sample = n_rows;
+  p.m_tiles = (int)((n_rows + kBM - 1) / kBM);
+  p.K = channels;
+  p.F = out_features;
+  p.n_tiles = (out_features + kBN - 1) / kBN;
+  return launch_gemm(p, static_cast<hipStream_t>(hip_stream)) == 0 ? AERIS_OK : AERIS_ERR_HIP_LAUNCH;
+}

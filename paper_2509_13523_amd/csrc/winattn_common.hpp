@@ -366,6 +366,22 @@ __device__ __forceinline__ void async_copy4(const void* src, uint32_t lds_base) 
                : "v"(src), "s"(__builtin_amdgcn_readfirstlane(lds_base))
                : "memory");
 }
+// The same copy with the source given as a wave-uniform 64-bit base plus a 32-bit unsigned
+// byte offset per lane; executed only if `enable` (wave-uniform) is non-zero.
+__device__ __forceinline__ void async_copy16_off(uint32_t offset, unsigned long long base,
+                                                 uint32_t lds_base, uint32_t enable = 1) {
+  asm volatile(
+      "s_cmp_eq_u32 %3, 0\n\t"
+      "s_cbranch_scc1 1f\n\t"
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %1\n"
+      "1:"
+      :
+      : "v"(offset), "s"(base), "s"(__builtin_amdgcn_readfirstlane(lds_base)),
+        "s"(__builtin_amdgcn_readfirstlane(enable))
+      : "memory", "scc");
+}
 __device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Makes the compiler finish the loads that produce `v` here (it then places its

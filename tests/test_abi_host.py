@@ -227,3 +227,29 @@ def test_layer_ops_workspace_grows_with_the_number_of_chunks():
     assert lib.aeris_rmsnorm_adaln_bwd_workspace_bytes(4 * 1036800, 1036800, 2048) == 2048 * 2 * 2048 * 4
     # tiny samples: at most one chunk per four rows
     assert lib.aeris_gate_residual_bwd_workspace_bytes(6, 6, 8) == 2 * 8 * 4
+
+
+def test_projections_reject_bad_arguments_before_launching():
+    lib = B.load()
+    a = ctypes.c_void_p(4096)
+    odd = ctypes.c_void_p(4096 + 8)
+    need = lib.aeris_norm_linear_workspace_bytes(512, 256, 128, 384)
+    # folded weights (2 samples x 384 x 128 bf16) + biases (2 x 384 fp32) + r (512 fp32), each
+    # rounded up to 256 bytes
+    assert need == 2 * 384 * 128 * 2 + 2 * 384 * 4 + 512 * 4
+    assert lib.aeris_norm_linear_workspace_bytes(512, 256, 96, 384) == 0       # 96 % 64
+    ok = lambda **kw: lib.aeris_norm_linear_fwd(
+        kw.get("x", a), a, a, a, kw.get("eps", 1e-6), a, kw.get("n", 512), kw.get("rps", 256),
+        kw.get("c", 128), kw.get("f", 384), kw.get("y", a), a, kw.get("ws", need), None)
+    assert ok(x=None) == -1 and ok(y=None) == -1
+    assert ok(c=96) == -3 and ok(f=12) == -3 and ok(rps=100) == -3
+    assert ok(c=32) == -2 and ok(c=16384) == -2 and ok(n=0) == -2 and ok(eps=-1.0) == -2
+    assert ok(x=odd) == -7
+    assert ok(ws=need - 1) == -8
+    sw = lambda **kw: lib.aeris_norm_linear_swiglu_fwd(
+        a, a, a, a, 1e-6, a, 512, 256, 128, kw.get("h", 192), kw.get("g", a), kw.get("uv", None),
+        a, kw.get("ws", need), None)
+    assert sw(g=None) == -1 and sw(h=100) == -3 and sw(h=0) == -2 and sw(ws=need - 1) == -8
+    lin = lambda **kw: lib.aeris_linear_fwd(kw.get("x", a), a, kw.get("n", 512), kw.get("c", 128),
+                                            kw.get("f", 384), kw.get("y", a), None)
+    assert lin(x=None) == -1 and lin(c=100) == -3 and lin(f=4) == -2 and lin(y=odd) == -7
