@@ -177,8 +177,9 @@ __global__ __launch_bounds__(kGemmWaves * 64, 1) void norm_linear_gemm_kernel(Ge
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
           acc[a][b] = mfma32(ao[kk & 1][a], bo[kk & 1][b], acc[a][b]);
-          // the next stage's copies, one per four products
-          if (b == 3) copy_piece(2 * kk + a, next_stage, (ks + 1) * kBK, more);
+          // the next stage's copies ride in the first half of the step, one per two products,
+          // so that they have the second half to land before the wait that opens the next step
+          if (kk < 2 && (b & 1)) copy_piece(4 * kk + 2 * a + (b >> 1), next_stage, (ks + 1) * kBK, more);
         }
       sched_fence();
     }
