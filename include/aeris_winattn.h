@@ -272,17 +272,6 @@ int aeris_winattn_rope_bwd_windows(const aeris_winattn_params* p, const aeris_ro
                                    const void* saved, void* workspace, size_t workspace_bytes,
                                    void* hip_stream);
 
-/*
- * Measurement aid (for callers that report a fraction of the attainable MFMA rate; not part
- * of the attention path): launches `blocks` workgroups of 256 threads, each wave issuing
- * 8 * iters v_mfma_f32_32x32x16_bf16 on register operands (32768 FLOP each) and nothing else.
- * random_operands != 0 fills the operands with pseudo-random bf16 values of unit scale, else
- * with small integers.  sink: device buffer of blocks * 256 floats, overwritten.
- * 1 <= blocks <= 65536, 1 <= iters.  FLOPs of a launch: blocks * 4 * iters * 8 * 32768.
- */
-int aeris_mfma_loop_probe(int32_t blocks, int32_t iters, int32_t random_operands, float* sink,
-                          void* hip_stream);
-
 /* Checks a parameter block without launching (host only): AERIS_OK or an error. */
 int aeris_winattn_validate(const aeris_winattn_params* p);
 

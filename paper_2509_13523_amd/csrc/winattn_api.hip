@@ -3,6 +3,8 @@
 // contract of every entry point.
 #include "aeris_winattn.h"
 
+#include "aeris_probe.h"
+
 #include <math.h>
 
 #include <atomic>

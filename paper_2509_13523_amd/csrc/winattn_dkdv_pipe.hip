@@ -300,7 +300,10 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
       st += step;
     }
   }
-  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // last accumulating MFMAs retire
+  // The accumulating MFMAs are assembly statements, so the compiler does not know their
+  // latency: wait it out (8 passes of 4 cycles plus write-back, with a wide margin) before the
+  // epilogue reads the accumulators.
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 
   if (!rg.valid) return;
   OutT* dkrow = dk + qkv_base + (long long)k_grid * p.qkv_tok;

@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import rope_oracle as ro
 from oracle import winattn_oracle as orc
 from paper_2509_13523_amd import binding as B
 from paper_2509_13523_amd import synth
@@ -78,8 +79,8 @@ def test_full_list_equals_plain_call_bitwise():
 
 @pytest.mark.parametrize("mode", [B.AERIS_ROPE_POS_WINDOW, B.AERIS_ROPE_POS_GRID])
 def test_rotary_attention_on_a_window_subset(mode):
-    """A rank's share with the rotary embedding: inside the listed windows the result is bit for
-    bit that of the full-grid rotary calls (which tests/test_gpu_rope.py holds to the oracle);
+    """A rank's share with the rotary embedding: inside the listed windows the result matches the
+    fp64 rotary oracle of the whole grid (and is bit for bit that of the full-grid rotary calls);
     nothing outside them is written, and q, k outside them are never read (NaN there)."""
     shape, win, shift, mask = (2, 36, 72, 2, 64), (12, 12), (6, 6), B.AERIS_MASK_SWIN
     Bn, H, W, nh, d = shape
@@ -108,11 +109,20 @@ def test_rotary_attention_on_a_window_subset(mode):
     assert torch.equal(o[:, inside], o_ref[:, inside])
     assert torch.equal(lse[:, :, inside], lse_ref[:, :, inside])
     assert torch.isnan(o[:, ~inside]).all() and torch.isnan(lse[:, :, ~inside]).all()
+    # against the oracle (not only against the full-grid HIP call)
+    q64, k64, v64, do64 = [synth.bf16_bits_to_f64(b) for b in bits]
+    pm = ro.POS_GRID if mode == B.AERIS_ROPE_POS_GRID else ro.POS_WINDOW
+    o_orc, lse_orc = ro.winattn_rope_fwd(q64, k64, v64, win, shift, mask, 100.0, pm)
+    g_orc = ro.winattn_rope_bwd(q64, k64, v64, do64, win, shift, mask, 100.0, pm)
+    ins = inside.cpu().numpy()
+    check("o", to_f64(o)[:, ins], o_orc[:, ins], True)
+    assert np.abs(to_f64(lse)[:, :, ins] - lse_orc[:, :, ins]).max() <= LSE_ABS
     for saved in (None, fws):           # rotating the share again, then from the forward's copies
         grads = [torch.full_like(tq, float("nan")) for _ in range(3)]
         B.aeris_winattn_rope_bwd_windows(sq, sk, sv, o, lse, sdo, win, shift, 100.0, mode, lst,
                                          *grads, mask=mask, saved=saved)
         torch.cuda.synchronize()
-        for g, ref in zip(grads, g_ref):
+        for name, g, ref, want in zip(("dq", "dk", "dv"), grads, g_ref, g_orc):
             assert torch.equal(g[:, inside], ref[:, inside])
             assert torch.isnan(g[:, ~inside]).all()
+            check(name, to_f64(g)[:, ins], want[:, ins], True)
