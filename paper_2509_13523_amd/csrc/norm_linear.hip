@@ -16,8 +16,8 @@
 // (global_load_lds_dwordx4), two stages of 64 KB, 16-byte chunks XOR-swizzled so that the
 // row-major ds_read_b128 operand fetches are conflict free; v_mfma_f32_32x32x16_bf16 with the
 // weight rows as the A operand and the token rows as the B operand, so that a lane owns one
-// token row of the output: the row scale is a per-lane scalar and a lane's 16 accumulator
-// values are four runs of four consecutive output features (8-byte stores).
+// token row of the output: the row scale is a per-lane scalar.  Results are staged through the
+// LDS and leave in 16-byte pieces, eight lanes per 128-byte row segment.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -185,52 +185,106 @@ __global__ __launch_bounds__(kGemmWaves * 64, 1) void norm_linear_gemm_kernel(Ge
     }
   }
 
-  // ---- epilogue: row scale, bias, (gate,) 8-byte stores of four consecutive features ------
+  // ---- epilogue: row scale, bias, (gate); results pass through the LDS so that they leave in
+  // 16-byte pieces, eight lanes per 128-byte row segment.  Each wave stages its 128 x 64 part
+  // in a region of its own (row pitch 144 bytes: 16-byte aligned, rows on different banks).
+  constexpr int kPitch = 144;
+  __syncthreads();                                   // every wave is done with the operand stages
   const float* bias = p.bias ? p.bias + (long long)sample * p.F : nullptr;
+  const uint32_t stage_w = lds0 + wave * (128 * kPitch);
+
+  // writes the wave's staged [128][64] bf16 block (8 chunks per row) to `dst` (row pitch ld):
+  // chunk c of a row goes to column col_of(c)
+  auto flush = [&](bf16_t* dst, long long ld, int chunks, auto col_of, int limit)
+      __attribute__((always_inline)) {
+    const int rows_per_inst = 64 / chunks;
+    const int r_in = lane / chunks, c = lane % chunks;
+    const int col = col_of(c);
+    for (int t = 0; t < 128 / rows_per_inst; ++t) {
+      const int ml = t * rows_per_inst + r_in;
+      const int m = wm * 128 + ml;
+      const u32x4 v = *reinterpret_cast<const AERIS_LDS u32x4*>(stage_w + ml * kPitch + c * 16);
+      if (m < valid_rows && col < limit)
+        *reinterpret_cast<u32x4*>(dst + (row0 + m) * ld + col) = v;
+    }
+  };
+
+  float rs[4];
 #pragma unroll
   for (int b = 0; b < 4; ++b) {
-    const int m = wm * 128 + b * 32 + li;
-    if (m >= valid_rows) continue;
-    const long long row = row0 + m;
-    const float rs = p.r ? p.r[row] : 1.f;
-    if (p.swiglu) {
+    int m = wm * 128 + b * 32 + li;
+    m = m < valid_rows ? m : valid_rows - 1;
+    rs[b] = p.r ? p.r[row0 + m] : 1.f;
+  }
+  auto stage_store = [&](int b, int col, float o0, float o1, float o2, float o3)
+      __attribute__((always_inline)) {
+    u32x2 v = {pack_bf16(o0, o1), pack_bf16(o2, o3)};
+    *reinterpret_cast<AERIS_LDS u32x2*>(stage_w + (b * 32 + li) * kPitch + col * 2) = v;
+  };
+
+  if (p.swiglu) {
+    const int jw = nt * (kBN / 2) + wn * 32;         // first gate column of this wave
+    f32x4 bu[4], bv[4];
 #pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        const int j = nt * (kBN / 2) + wn * 32 + 8 * vq + 4 * g;
-        if (j >= hidden) continue;
-        float u[4], v[4];
-        f32x4 bu = {0.f, 0.f, 0.f, 0.f}, bv = bu;
-        if (bias) {
-          bu = *reinterpret_cast<const f32x4*>(bias + j);
-          bv = *reinterpret_cast<const f32x4*>(bias + hidden + j);
-        }
+    for (int vq = 0; vq < 4; ++vq) {
+      int j = jw + 8 * vq + 4 * g;
+      j = j < hidden ? j : hidden - 4;
+      bu[vq] = bias ? *reinterpret_cast<const f32x4*>(bias + j) : f32x4{0.f, 0.f, 0.f, 0.f};
+      bv[vq] = bias ? *reinterpret_cast<const f32x4*>(bias + hidden + j) : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    // u and v (kept in registers), staged as [u 32 | v 32] for the optional uv output
+    float uu[4][16], vv[4][16];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          u[e] = __builtin_fmaf(acc[0][b][4 * vq + e], rs, bu[e]);
-          v[e] = __builtin_fmaf(acc[1][b][4 * vq + e], rs, bv[e]);
-        }
-        if (p.y) {
-          store4(p.y + row * p.F + j, u[0], u[1], u[2], u[3]);
-          store4(p.y + row * p.F + hidden + j, v[0], v[1], v[2], v[3]);
-        }
-        store4(p.g + row * hidden + j, silu(u[0]) * v[0], silu(u[1]) * v[1], silu(u[2]) * v[2],
-               silu(u[3]) * v[3]);
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        uu[b][i] = __builtin_fmaf(acc[0][b][i], rs[b], bu[i >> 2][i & 3]);
+        vv[b][i] = __builtin_fmaf(acc[1][b][i], rs[b], bv[i >> 2][i & 3]);
       }
-    } else {
+    if (p.y) {
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int b = 0; b < 4; ++b)
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) {
-          const int f = nt * kBN + wn * 64 + a * 32 + 8 * vq + 4 * g;
-          if (f >= p.F) continue;
-          float o[4];
-          f32x4 b4 = {0.f, 0.f, 0.f, 0.f};
-          if (bias) b4 = *reinterpret_cast<const f32x4*>(bias + f);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = __builtin_fmaf(acc[a][b][4 * vq + e], rs, b4[e]);
-          store4(p.y + row * p.F + f, o[0], o[1], o[2], o[3]);
+          stage_store(b, 8 * vq + 4 * g, uu[b][4 * vq], uu[b][4 * vq + 1], uu[b][4 * vq + 2],
+                      uu[b][4 * vq + 3]);
+          stage_store(b, 32 + 8 * vq + 4 * g, vv[b][4 * vq], vv[b][4 * vq + 1], vv[b][4 * vq + 2],
+                      vv[b][4 * vq + 3]);
         }
+      // chunk c: c < 4 -> u columns jw + 8c, else v columns hidden + jw + 8(c - 4); a column
+      // past `hidden` (ragged last tile) is marked by F, which the limit rejects
+      flush(p.y, p.F, 8, [&](int c) {
+        const int j = jw + 8 * (c & 3);
+        return j < hidden ? (c < 4 ? j : hidden + j) : p.F;
+      }, p.F);
     }
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq)
+        stage_store(b, 8 * vq + 4 * g, silu(uu[b][4 * vq]) * vv[b][4 * vq],
+                    silu(uu[b][4 * vq + 1]) * vv[b][4 * vq + 1],
+                    silu(uu[b][4 * vq + 2]) * vv[b][4 * vq + 2],
+                    silu(uu[b][4 * vq + 3]) * vv[b][4 * vq + 3]);
+    flush(p.g, hidden, 4, [&](int c) { return jw + 8 * c; }, hidden);
+  } else {
+    const int fw = nt * kBN + wn * 64;               // first feature of this wave
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) {
+        int f = fw + a * 32 + 8 * vq + 4 * g;
+        f = f < p.F ? f : p.F - 4;
+        const f32x4 b4 = bias ? *reinterpret_cast<const f32x4*>(bias + f) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          stage_store(b, a * 32 + 8 * vq + 4 * g,
+                      __builtin_fmaf(acc[a][b][4 * vq], rs[b], b4[0]),
+                      __builtin_fmaf(acc[a][b][4 * vq + 1], rs[b], b4[1]),
+                      __builtin_fmaf(acc[a][b][4 * vq + 2], rs[b], b4[2]),
+                      __builtin_fmaf(acc[a][b][4 * vq + 3], rs[b], b4[3]));
+      }
+    flush(p.y, p.F, 8, [&](int c) { return fw + 8 * c; }, p.F);
   }
 }
 
@@ -308,8 +362,11 @@ bool bad16(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15) != 
 int launch_gemm(GemmParams p, hipStream_t stream) {
   p.m_tiles_per_sample = (int)((p.rows_per_sample + kBM - 1) / kBM);
   if (!allow_full_lds<norm_linear_gemm_kernel>()) return -1;
-  return launch_kernel(norm_linear_gemm_kernel, dim3(gemm_grid(p)), dim3(kGemmWaves * 64),
-                       2 * kStageBytes, stream, p);
+  // two operand stages; the epilogue reuses them as eight 128 x 144-byte staging regions
+  constexpr size_t kSmem = kGemmWaves * 128 * 144 > 2 * kStageBytes ? kGemmWaves * 128 * 144
+                                                                    : 2 * kStageBytes;
+  return launch_kernel(norm_linear_gemm_kernel, dim3(gemm_grid(p)), dim3(kGemmWaves * 64), kSmem,
+                       stream, p);
 }
 
 struct Folded {
