@@ -7,7 +7,11 @@ parameters; the oracle is fp64 throughout and rounds nothing.  The kernels multi
 raw rows x are bf16 as given, the folded weight W_fc w_c (1 + gamma_bc) is rounded to bf16 once
 (half an ulp, 2^-8 relative at worst, per element), products accumulate in fp32, the row scale and
 the bias are applied in fp32 and the result is rounded to bf16.  Tolerances, written out in
-`close`: relative L2 of a whole tensor <= 3e-3 (the bound of the other layer operations), and per
+`close`: relative L2 of a whole tensor <= 3e-3 (the bound of the other layer operations; the
+folded-weight rounding and the output rounding are each uniform within half an ulp, 2^-9 / sqrt 3
+= 1.1e-3 in relative L2, together 1.6e-3, measured 1.6e-3 to 2.4e-3), 4e-3 for the gated output
+g = silu(u) v, which multiplies two such values and is rounded once more (expected
+sqrt(2 * 1.6e-3^2 + 1.1e-3^2) = 2.5e-3, measured 2.7e-3 to 3.0e-3), and per
 element  |err| <= 2^-7 |ref| (output rounding, with a boundary step)
                   + 2^-8 r_i sum_c |x_ic| |Wf_fc|  (first-order effect of rounding the folded weight)
                   + 1e-5 |x_i|.|Wf_f| r_i          (fp32 accumulation of 2^11 terms).
@@ -25,6 +29,7 @@ import parity_log
 pytestmark = pytest.mark.gpu
 
 REL_L2 = 3e-3
+REL_L2_GATED = 4e-3
 
 
 def to_dev(bits):
@@ -68,7 +73,7 @@ def rounding_bound(c, eps, rows):
     return (2.0 ** -8 + 1e-5) * out
 
 
-def close(name, got, ref, bound):
+def close(name, got, ref, bound, rel_l2=REL_L2):
     got = to_f64(got)
     assert np.isfinite(got).all(), name
     err = np.abs(got - ref)
@@ -79,7 +84,7 @@ def close(name, got, ref, bound):
     worst = np.argmax(err - allow)
     assert (err <= allow).all(), "%s: err %.3e > %.3e at %d" % (name, err.flat[worst],
                                                                 allow.flat[worst], worst)
-    assert rel <= REL_L2, "%s rel_l2 %.3e" % (name, rel)
+    assert rel <= rel_l2, "%s rel_l2 %.3e" % (name, rel)
 
 
 PROJ_CASES = [
@@ -121,7 +126,8 @@ def test_norm_linear_swiglu_fwd(n_samples, rows, channels, hidden):
     # g = silu(u) v: |d g| <= |silu'(u)| |v| |d u| + |silu(u)| |d v|, |silu'| <= 1.1
     u, v = uv_ref[:, :hidden], uv_ref[:, hidden:]
     silu_u = u / (1.0 + np.exp(-u))
-    close("g", g, g_ref, 1.1 * np.abs(v) * bound[:, :hidden] + np.abs(silu_u) * bound[:, hidden:])
+    close("g", g, g_ref, 1.1 * np.abs(v) * bound[:, :hidden] + np.abs(silu_u) * bound[:, hidden:],
+          rel_l2=REL_L2_GATED)
     # without the packed up-projection: same g, nothing else written
     g2, none = B.aeris_norm_linear_swiglu_fwd(c["tx"], c["tw"], c["tgamma"], c["tbeta"], eps,
                                               c["tweight"], rows, want_uv=False)
