@@ -259,6 +259,13 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
   }
   if (rg.wave_active) stage_a(0);
   int a_buf = 0, c_buf = 0;   // buffer index `rm` / `tr`,`st` point into
+  // Two of the four waves take the tile barrier one stage earlier (before the accumulating
+  // stage of block 0 instead of after it).  Both places lie after every read of the previous
+  // tile's buffer and before the first read of the next tile, so the barrier means the same
+  // for both; but from then on one pair of waves is in a vector stage (light on the LDS) while
+  // the other is in an accumulating stage (transposing reads at the rate the LDS delivers),
+  // instead of all four hitting the LDS, and then the vector pipe, together.
+  const bool early_barrier = wave >= 2;
 
   for (int qt = qt_begin; qt < qt_end; ++qt) {
     const bool more = qt + 1 < qt_end;
@@ -266,7 +273,7 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
     // first half: A(tile qt, block 1) with B(tile qt, block 0); then C(block 0)
     if (rg.wave_active) {
       run_ab(true, s0, dp0, s1, dp1, Tl::kSubBytes, 0, qt * kStream, false, 0, 0);
-      stage_c(0);
+      if (!early_barrier) stage_c(0);
     }
     // tile qt+1 must be visible before stage A touches it; this barrier also
     // retires every reader of tile qt-1, whose buffer the new fill reuses
@@ -281,6 +288,7 @@ __global__ __launch_bounds__(kThreads, 1) void winattn_dkdv_pipe_kernel(
 #pragma unroll
       for (int kk = 0; kk < kNK; ++kk) la.rm[kk] += step;
     }
+    if (early_barrier && rg.wave_active) stage_c(0);
     // second half: A(tile qt+1, block 0) with B(tile qt, block 1); then C(block 1)
     if (rg.wave_active) {
       run_ab(more, s1, dp1, s0, dp0, 0, 32 * 4, qt * kStream + 32, do_fill, fill_buf, fill_t0);
