@@ -10,8 +10,10 @@ the two projections done by torch's bf16 matmul (the layer's GEMMs belong to the
 and its backward pass through the matching entry points.  The reference chains the fp64 oracles
 (oracle/block_oracle.py, oracle/rope_oracle.py) with fp64 matrix products, rounding to bf16
 exactly where the GPU path stores a bf16 tensor (h, qkv, a, y, and the gradients handed from one
-stage to the next), so that both sides feed the same kind of operands to every stage.
-(AERIS paper, Model Architecture section.)"""
+stage to the next), so that both sides feed the same kind of operands to every stage; and,
+beside it, the same chain with nothing rounded at all (the plain definition), under bounds that
+are wider by the bf16 roundings of the hand-overs (measured: at most 6.2e-3 relative L2, on the
+gradient of the packed projection).  (AERIS paper, Model Architecture section.)"""
 import ctypes
 
 import numpy as np
@@ -22,6 +24,7 @@ from oracle import block_oracle as bo
 from oracle import rope_oracle as ro
 from paper_2509_13523_amd import binding as B
 from paper_2509_13523_amd import synth
+import parity_log
 
 pytestmark = pytest.mark.gpu
 
@@ -60,26 +63,34 @@ def test_attention_half_of_a_layer_forward_and_backward():
     beta = (0.3 * rng.standard_normal((Bn, C))).astype(np.float32).astype(np.float64)
     alpha = (0.8 * rng.standard_normal((Bn, C))).astype(np.float32).astype(np.float64)
 
-    # ------------------------------------------------------------------ reference (fp64 + rounding)
-    h, _ = bo.rmsnorm_adaln_fwd(x, w, gamma, beta, eps, rps)
-    h = rb(h)
-    qkv = rb(h @ wqkv.T).reshape(Bn, H, W, 3, nh, d)
-    q, k, v = qkv[:, :, :, 0], qkv[:, :, :, 1], qkv[:, :, :, 2]
-    a, _ = ro.winattn_rope_fwd(q, k, v, win, shift, mask, base, ro.POS_WINDOW)
-    a = rb(a)
-    y = rb(a.reshape(N, C) @ wo.T)
-    out = bo.gate_residual_fwd(x, y, alpha, rps)
-    # backward
-    _, dy, dalpha = bo.gate_residual_bwd(y, alpha, dout, rps)
-    dy = rb(dy)
-    dwo = dy.T @ a.reshape(N, C)
-    da = rb(dy @ wo).reshape(Bn, H, W, nh, d)
-    dq, dk, dv = ro.winattn_rope_bwd(q, k, v, da, win, shift, mask, base, ro.POS_WINDOW)
-    dqkv = rb(np.stack([dq, dk, dv], axis=3)).reshape(N, 3 * C)
-    dwqkv = dqkv.T @ h
-    dh = rb(dqkv @ wqkv)
-    dx_norm, dw, dgamma, dbeta = bo.rmsnorm_adaln_bwd(x, w, gamma, beta, eps, rps, dh)
-    dx = dout + dx_norm      # the residual path hands dout through
+    # ------------------------------------------------------------------ reference chain (fp64);
+    # rnd is applied wherever the GPU path stores a bf16 tensor: rb for the like-for-like
+    # comparison, the identity for the plain definition with no rounding anywhere
+    def chain(rnd):
+        h, _ = bo.rmsnorm_adaln_fwd(x, w, gamma, beta, eps, rps)
+        h = rnd(h)
+        qkv = rnd(h @ wqkv.T).reshape(Bn, H, W, 3, nh, d)
+        q, k, v = qkv[:, :, :, 0], qkv[:, :, :, 1], qkv[:, :, :, 2]
+        a, _ = ro.winattn_rope_fwd(q, k, v, win, shift, mask, base, ro.POS_WINDOW)
+        a = rnd(a)
+        y = rnd(a.reshape(N, C) @ wo.T)
+        out = bo.gate_residual_fwd(x, y, alpha, rps)
+        # backward
+        _, dy, dalpha = bo.gate_residual_bwd(y, alpha, dout, rps)
+        dy = rnd(dy)
+        dwo = dy.T @ a.reshape(N, C)
+        da = rnd(dy @ wo).reshape(Bn, H, W, nh, d)
+        dq, dk, dv = ro.winattn_rope_bwd(q, k, v, da, win, shift, mask, base, ro.POS_WINDOW)
+        dqkv = rnd(np.stack([dq, dk, dv], axis=3)).reshape(N, 3 * C)
+        dwqkv = dqkv.T @ h
+        dh = rnd(dqkv @ wqkv)
+        dx_norm, dw, dgamma, dbeta = bo.rmsnorm_adaln_bwd(x, w, gamma, beta, eps, rps, dh)
+        dx = dout + dx_norm      # the residual path hands dout through
+        return dict(h=h, qkv=qkv.reshape(N, 3 * C), a=a.reshape(N, C), out=out, dy=dy, dqkv=dqkv,
+                    dx=dx, dalpha=dalpha, dwo=dwo, dwqkv=dwqkv, dw=dw, dgamma=dgamma, dbeta=dbeta)
+
+    ref = chain(rb)
+    plain = chain(lambda t: t)
 
     # ------------------------------------------------------------------ GPU path
     tx, tdout = dev_bf16(x), dev_bf16(dout)
@@ -122,17 +133,23 @@ def test_attention_half_of_a_layer_forward_and_backward():
     torch.cuda.synchronize()
 
     # ------------------------------------------------------------------ comparison
-    # h and qkv agree with the rounded reference almost to the bit; from the attention on, both
-    # sides carry the attention tolerance (5e-3 relative L2) through the rest of the chain
-    for name, got, ref, tol in (("h", f64(th), h, 1e-4), ("qkv", f64(tqkv), qkv.reshape(N, 3 * C), 1e-3),
-                                ("a", f64(ta), a.reshape(N, C), 5e-3), ("out", f64(tout), out, 5e-3),
-                                ("dy", f64(tdy), dy, 1e-4), ("dqkv", f64(tdqkv), dqkv, 8e-3),
-                                ("dx", f64(tdx), dx, 8e-3), ("dalpha", f64(tdalpha), dalpha, 8e-3),
-                                ("dwo", f64(tdwo), dwo, 8e-3), ("dwqkv", f64(tdwqkv), dwqkv, 8e-3),
-                                ("dw", f64(tdw), dw, 8e-3), ("dgamma", f64(tdgamma), dgamma, 8e-3),
-                                ("dbeta", f64(tdbeta), dbeta, 8e-3)):
-        assert np.isfinite(got).all(), name
-        assert rel_l2(got, ref) <= tol, "%s rel_l2 %.3e" % (name, rel_l2(got, ref))
+    # like for like (reference rounded where the GPU path stores bf16): h and qkv agree almost to
+    # the bit; from the attention on, both sides carry the attention tolerance (5e-3 relative L2)
+    # through the rest of the chain.  Against the plain definition (nothing rounded) every
+    # hand-over adds one bf16 rounding (1.1e-3 in relative L2) on top: bounds 3e-3 before the
+    # attention, 1e-2 after it.
+    got = dict(h=th, qkv=tqkv, a=ta, out=tout, dy=tdy, dqkv=tdqkv, dx=tdx, dalpha=tdalpha, dwo=tdwo,
+               dwqkv=tdwqkv, dw=tdw, dgamma=tdgamma, dbeta=tdbeta)
+    tol = dict(h=1e-4, qkv=1e-3, a=5e-3, out=5e-3, dy=1e-4)
+    tol_plain = dict(h=3e-3, qkv=3e-3, dy=3e-3)
+    for name, t in got.items():
+        g64 = f64(t)
+        assert np.isfinite(g64).all(), name
+        e_like, e_plain = rel_l2(g64, ref[name]), rel_l2(g64, plain[name])
+        parity_log.add(name, "bf16", e_like, 0.0, 0.0, tol.get(name, 8e-3))
+        parity_log.add(name + "*", "bf16", e_plain, 0.0, 0.0, tol_plain.get(name, 1e-2))
+        assert e_like <= tol.get(name, 8e-3), "%s rel_l2 %.3e" % (name, e_like)
+        assert e_plain <= tol_plain.get(name, 1e-2), "%s rel_l2 vs unrounded %.3e" % (name, e_plain)
 
 
 def test_swiglu_half_of_a_layer_forward_and_backward():
