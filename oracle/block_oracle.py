@@ -143,6 +143,17 @@ def linear_fwd(x, weight):
     return x @ weight.T
 
 
+def linear_bwd(x, weight, dy):
+    """Gradients of y = x W^T (the chain rule on a bilinear map):
+    dx [N, C] = dy W,   dW [F, C] = dy^T x   for dy [N, F]."""
+    x = np.asarray(x, dtype=np.float64)
+    weight = np.asarray(weight, dtype=np.float64)
+    dy = np.asarray(dy, dtype=np.float64)
+    if weight.ndim != 2 or weight.shape[1] != x.shape[1] or dy.shape != (x.shape[0], weight.shape[0]):
+        raise ValueError("x [N, C], weight [F, C] and dy [N, F] do not fit")
+    return dy @ weight, dy.T @ x
+
+
 def norm_linear_fwd(x, w, gamma, beta, eps, rows_per_sample, weight):
     """Projection of the normalised, modulated rows: y = h W^T, h as in rmsnorm_adaln_fwd."""
     h, _ = rmsnorm_adaln_fwd(x, w, gamma, beta, eps, rows_per_sample)

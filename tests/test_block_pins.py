@@ -317,3 +317,50 @@ def test_norm_linear_invariants():
         folded = weight * (w * (1.0 + gamma[b]))[None, :]
         np.testing.assert_allclose(r[sl, None] * (x[sl] @ folded.T) + beta[b] @ weight.T, y[sl],
                                    rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- backward of a projection
+def test_linear_bwd_worked_by_hand():
+    # y = x W^T with x = (1, 2), W = [[3, 4], [5, 6], [7, 8]], dy = (1, 0, -1):
+    # dx = dy W = (3 - 7, 4 - 8); dW = dy^T x = rows (1, 2), (0, 0), (-1, -2)
+    x = np.array([[1.0, 2.0]])
+    weight = np.array([[3.0, 4.0], [5.0, 6.0], [7.0, 8.0]])
+    dy = np.array([[1.0, 0.0, -1.0]])
+    dx, dw = bo.linear_bwd(x, weight, dy)
+    np.testing.assert_array_equal(dx, [[-4.0, -4.0]])
+    np.testing.assert_array_equal(dw, [[1.0, 2.0], [0.0, 0.0], [-1.0, -2.0]])
+
+
+def test_linear_bwd_against_scalar_loops_autograd_and_differences():
+    rng = np.random.default_rng(77)
+    n, c, f = 7, 5, 4                       # all different: a transposed operand changes a shape
+    x, weight, dy = _rand(rng, n, c), _rand(rng, f, c), _rand(rng, n, f)
+    dx, dw = bo.linear_bwd(x, weight, dy)
+    assert dx.shape == (n, c) and dw.shape == (f, c)
+    for i in range(n):
+        for k in range(c):
+            assert dx[i, k] == pytest.approx(sum(dy[i, j] * weight[j, k] for j in range(f)), abs=1e-13)
+    for j in range(f):
+        for k in range(c):
+            assert dw[j, k] == pytest.approx(sum(dy[i, j] * x[i, k] for i in range(n)), abs=1e-13)
+    tx = torch.tensor(x, requires_grad=True)
+    tw = torch.tensor(weight, requires_grad=True)
+    torch.nn.functional.linear(tx, tw).backward(torch.tensor(dy))
+    np.testing.assert_allclose(dx, tx.grad.numpy(), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(dw, tw.grad.numpy(), rtol=0, atol=1e-13)
+    # central differences of L = <y, dy> through the forward oracle (L is bilinear: exact up to rounding)
+    loss = lambda xx, ww: float(np.sum(bo.linear_fwd(xx, ww) * dy))
+    h = 1e-3
+    for (i, k) in [(0, 0), (3, 4), (6, 2)]:
+        e = np.zeros_like(x); e[i, k] = h
+        assert (loss(x + e, weight) - loss(x - e, weight)) / (2 * h) == pytest.approx(dx[i, k], abs=1e-9)
+    for (j, k) in [(0, 0), (3, 4), (1, 2)]:
+        e = np.zeros_like(weight); e[j, k] = h
+        assert (loss(x, weight + e) - loss(x, weight - e)) / (2 * h) == pytest.approx(dw[j, k], abs=1e-9)
+    # the two gradients pair up: <dx, x> = <dW, W> = <y, dy>
+    assert np.sum(dx * x) == pytest.approx(np.sum(dw * weight), rel=1e-13)
+    assert np.sum(dx * x) == pytest.approx(loss(x, weight), rel=1e-13)
+    with pytest.raises(ValueError):
+        bo.linear_bwd(x, weight, dy.T)
+    with pytest.raises(ValueError):
+        bo.linear_bwd(x, weight.T, dy)
