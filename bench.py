@@ -120,11 +120,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS) + ["layer_ops", "qkv_proj"],
+    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS) + ["layer_ops", "qkv_proj", "qkv_proj_bwd"],
                     help="layer_ops: the element-wise kernels of include/aeris_layer_ops.h on the "
                          "headline grid's tokens (a bandwidth figure, not the headline metric); "
                          "qkv_proj: the fused RMSNorm + modulation + QKV projection and the fused "
-                         "SwiGLU up-projection on the same tokens (bf16 MFMA TFLOP/s)")
+                         "SwiGLU up-projection on the same tokens (bf16 MFMA TFLOP/s); "
+                         "qkv_proj_bwd: the two gradient GEMMs of the QKV projection")
     ap.add_argument("--channels", type=int, default=2048, help="row width for --workload layer_ops")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-pairs", type=int, default=64)
@@ -150,6 +151,8 @@ def main():
         return bench_layer_ops(args)
     if args.workload == "qkv_proj":
         return bench_projections(args)
+    if args.workload == "qkv_proj_bwd":
+        return bench_projection_bwd(args)
     wl = WORKLOADS[args.workload]
     shape, win, mask = wl["shape"], wl["win"], wl["mask"]
     Bn, H, W, nh, d = shape
@@ -456,6 +459,84 @@ def bench_projections(args):
                    "vendor_gemm_qkv_shape_ms": round(vendor_ms, 3),
                    "vendor_gemm_qkv_shape_tflops": round(2.0 * n * C * F / (vendor_ms * 1e-3) / 1e12, 1)},
         "roofline": {"kernel": "norm_linear_gemm_kernel (%s)" % slow[0], "bound": "mfma",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None}}))
+
+
+def bench_projection_bwd(args):
+    """One step = the two gradient GEMMs of the QKV projection (dx = dy W, dW = dy^T x) on
+    4 x 720 x 1440 token rows, 2048 channels, 6144 features.  FLOPs = 2 * rows * channels *
+    features each; torch's bf16 matmul (the vendor GEMM) on the same two products beside them."""
+    import torch
+    from paper_2509_13523_amd import binding as B
+    n, C = 4 * 720 * 1440, args.channels
+    F = 3 * C
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    gen = torch.Generator(device=dev).manual_seed(7200)
+    x = torch.randn(n, C, device=dev, dtype=torch.bfloat16, generator=gen)
+    wqkv = (torch.randn(F, C, device=dev, generator=gen) / C ** 0.5).to(torch.bfloat16)
+    dy = torch.empty(n, F, device=dev, dtype=torch.bfloat16)
+    for i in range(0, n, n // 8):
+        dy[i:i + n // 8] = torch.randn(n // 8, F, device=dev, dtype=torch.bfloat16, generator=gen)
+    dx = torch.empty_like(x)
+    dw = torch.empty(F, C, device=dev, dtype=torch.float32)
+    ws = torch.empty(B.aeris_linear_bwd_workspace_bytes(n, C, F), dtype=torch.uint8, device=dev)
+    fl = 2.0 * n * C * F
+    ops = [("dx", lambda: B.aeris_linear_bwd(None, wqkv, dy, want_dweight=False, dx=dx, workspace=ws)),
+           ("dweight", lambda: B.aeris_linear_bwd(x, wqkv, dy, want_dx=False, dweight=dw, workspace=ws))]
+    dw16 = torch.empty(F, C, device=dev, dtype=torch.bfloat16)
+    vendor = [("dx", lambda: torch.matmul(dy, wqkv, out=dx)),
+              ("dweight", lambda: torch.matmul(dy.t(), x, out=dw16))]
+
+    def timed(fn, reps):
+        evs = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        return sorted(a.elapsed_time(b) for a, b in evs)
+
+    for _ in range(args.warmup):
+        for _, fn in ops:
+            fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev = {name: [] for name, _ in ops}
+    for _ in range(args.steps):
+        for name, fn in ops:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            ev[name].append((e0, e1))
+    torch.cuda.synchronize()
+    step_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    per = {}
+    for name, _ in ops:
+        ts = sorted(a.elapsed_time(b) for a, b in ev[name])
+        per[name] = {"median_ms": round(ts[len(ts) // 2], 3), "min_ms": round(ts[0], 3),
+                     "tflops": round(fl / (ts[len(ts) // 2] * 1e-3) / 1e12, 1)}
+    ven = {}
+    for name, fn in vendor:
+        fn()
+        ts = timed(fn, 3)
+        ven[name] = {"median_ms": round(ts[1], 3), "tflops": round(fl / (ts[1] * 1e-3) / 1e12, 1)}
+    slow = min(per, key=lambda k: per[k]["tflops"])
+    achieved = per[slow]["tflops"]
+    print(json.dumps({
+        "metric": "projection_backward_tflops", "value": round(2 * fl / (step_ms * 1e-3) / 1e12, 1),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "qkv_proj_bwd: %d token rows, %d channels, %d features: dx = dy W "
+                               "(bf16) and dW = dy^T x (fp32)" % (n, C, F), "kernels": per,
+                   "vendor_gemm_same_products": ven},
+        "roofline": {"kernel": "%s (%s)" % ("linear_wgrad_kernel" if slow == "dweight"
+                                            else "norm_linear_gemm_kernel", slow), "bound": "mfma",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None}}))
 

@@ -143,6 +143,24 @@ int aeris_norm_linear_swiglu_fwd(const void* x, const float* w, const float* gam
 int aeris_linear_fwd(const void* x, const void* weight, int64_t n_rows, int32_t channels,
                      int32_t out_features, void* y, void* hip_stream);
 
+/*
+ * Gradients of a projection y = x weight^T (the backward pass of each projection of a layer):
+ *     dx      [n_rows, channels]       = dy weight        (bf16, fp32 accumulation)
+ *     dweight [out_features, channels] = dy^T x           (fp32)
+ * x [n_rows, channels], weight [out_features, channels], dy [n_rows, out_features]: bf16, rows
+ * contiguous, read only.  Either output may be NULL (then its operand x or weight may be too).
+ * dweight is overwritten, not accumulated into; it is the sum of per-row-range partial results
+ * added in a fixed order, so it does not depend on the schedule.
+ * Limits: channels % 64 == 0, out_features % 64 == 0, n_rows % 64 == 0,
+ * out_features * channels < 2^31.  workspace: >= aeris_linear_bwd_workspace_bytes(...) bytes
+ * (the transposed weight and the partial results), 16-byte aligned, contents undefined before
+ * and after.  Errors as elsewhere: AERIS_ERR_ codes, checked before any launch.
+ */
+size_t aeris_linear_bwd_workspace_bytes(int64_t n_rows, int32_t channels, int32_t out_features);
+int aeris_linear_bwd(const void* x, const void* weight, const void* dy, int64_t n_rows,
+                     int32_t channels, int32_t out_features, void* dx, float* dweight,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

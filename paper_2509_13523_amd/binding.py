@@ -29,7 +29,8 @@ EXPORTS = ("aeris_winattn_fwd", "aeris_winattn_bwd", "aeris_winattn_bwd_stages",
            "aeris_rmsnorm_adaln_bwd", "aeris_gate_residual_fwd",
            "aeris_gate_residual_bwd_workspace_bytes", "aeris_gate_residual_bwd",
            "aeris_swiglu_fwd", "aeris_swiglu_bwd", "aeris_norm_linear_workspace_bytes",
-           "aeris_norm_linear_fwd", "aeris_norm_linear_swiglu_fwd", "aeris_linear_fwd")
+           "aeris_norm_linear_fwd", "aeris_norm_linear_swiglu_fwd", "aeris_linear_fwd",
+           "aeris_linear_bwd_workspace_bytes", "aeris_linear_bwd")
 
 
 class aeris_winattn_params(ctypes.Structure):
@@ -138,6 +139,10 @@ def load():
     lib.aeris_norm_linear_swiglu_fwd.restype = ctypes.c_int
     lib.aeris_linear_fwd.argtypes = [vp, vp, i64, i32, i32, vp, vp]
     lib.aeris_linear_fwd.restype = ctypes.c_int
+    lib.aeris_linear_bwd_workspace_bytes.argtypes = [i64, i32, i32]
+    lib.aeris_linear_bwd_workspace_bytes.restype = sz
+    lib.aeris_linear_bwd.argtypes = [vp, vp, vp, i64, i32, i32, vp, vp, vp, sz, vp]
+    lib.aeris_linear_bwd.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -637,3 +642,34 @@ def aeris_linear_fwd(x, weight, y=None):
     if rc != 0:
         raise AerisError(rc, "aeris_linear_fwd")
     return y
+
+
+def aeris_linear_bwd_workspace_bytes(n_rows, channels, out_features):
+    return load().aeris_linear_bwd_workspace_bytes(n_rows, channels, out_features)
+
+
+def aeris_linear_bwd(x, weight, dy, want_dx=True, want_dweight=True, dx=None, dweight=None,
+                     workspace=None):
+    """Gradients of y = x weight^T: dx = dy weight (bf16), dweight = dy^T x (fp32)."""
+    import torch
+    n, f = _rows(dy)
+    assert weight.is_cuda and weight.dtype == torch.bfloat16 and weight.is_contiguous()
+    assert weight.dim() == 2 and weight.shape[0] == f
+    c = weight.shape[1]
+    if want_dweight:
+        assert _rows(x) == (n, c)
+    if want_dx and dx is None:
+        dx = torch.empty((n, c), dtype=torch.bfloat16, device=dy.device)
+    if want_dweight and dweight is None:
+        dweight = torch.empty((f, c), dtype=torch.float32, device=dy.device)
+    if workspace is None:
+        workspace = torch.empty(max(aeris_linear_bwd_workspace_bytes(n, c, f), 16), dtype=torch.uint8,
+                                device=dy.device)
+    rc = load().aeris_linear_bwd(x.data_ptr() if want_dweight else None, weight.data_ptr(),
+                                 dy.data_ptr(), n, c, f,
+                                 dx.data_ptr() if want_dx else None,
+                                 dweight.data_ptr() if want_dweight else None,
+                                 workspace.data_ptr(), workspace.numel(), _stream())
+    if rc != 0:
+        raise AerisError(rc, "aeris_linear_bwd")
+    return (dx if want_dx else None), (dweight if want_dweight else None)

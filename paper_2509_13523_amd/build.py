@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libaeris_winattn.so")
 SOURCES = ["winattn_api.hip", "winattn_fwd.hip", "winattn_bwd.hip", "winattn_dkdv_pipe.hip", "winattn_rope.hip", "winattn_probe.hip",
-           "layer_ops.hip", "norm_linear.hip"]
+           "layer_ops.hip", "norm_linear.hip", "linear_bwd.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", INCLUDE, "-I", CSRC]

@@ -23,6 +23,7 @@
 
 #include "aeris_layer_ops.h"
 #include "aeris_winattn.h"
+#include "projection_gemm.hpp"
 #include "winattn_common.hpp"
 #include "winattn_launch.hpp"
 
@@ -36,22 +37,6 @@ constexpr int kGemmWaves = 8;
 constexpr int kPartBytes = kBN * kBK * 2;            // 32 KB: weight rows, then token rows
 constexpr int kStageBytes = 2 * kPartBytes;
 using Sub = Tile<64, kGemmWaves>;        // 64 rows x 64 channels, swizzled chunks
-
-struct GemmParams {
-  const bf16_t* x;             // [n_rows, K]
-  const bf16_t* w;             // [F, K], or per sample [n_samples][F, K]
-  long long w_sample_stride;   // elements between the samples' matrices (0: one for all)
-  const float* r;              // [n_rows] row scale, or null
-  const float* bias;           // [n_samples][F], or null
-  bf16_t* y;                   // [n_rows, F]: the projection (plain), or uv (SwiGLU, may be null)
-  bf16_t* g;                   // SwiGLU: [n_rows, F / 2]
-  long long rows_per_sample;
-  int m_tiles_per_sample;
-  int m_tiles;                 // n_samples * m_tiles_per_sample
-  int n_tiles;
-  int K, F;
-  int swiglu;
-};
 
 // Workgroup id -> (token tile, feature tile).  Consecutive ids go to the eight XCDs in turn;
 // the 32 workgroups an XCD runs at a time are 8 token tiles x 4 feature tiles, so every
@@ -341,25 +326,34 @@ __global__ __launch_bounds__(256) void fold_weights_kernel(const bf16_t* __restr
 
 size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
 
-int check_projection(int64_t n_rows, int64_t rows_per_sample, int32_t channels, int32_t features) {
-  if (n_rows <= 0 || rows_per_sample <= 0 || channels <= 0 || features <= 0)
-    return AERIS_ERR_INVALID_SHAPE;
-  if (channels < kBK || channels > AERIS_MAX_PROJECTION_CHANNELS || features < 8)
-    return AERIS_ERR_INVALID_SHAPE;
-  if (channels % kBK != 0 || features % 8 != 0 || n_rows % rows_per_sample != 0)
-    return AERIS_ERR_NOT_DIVISIBLE;
+}  // namespace
+
+int projection_gemm_check(long long n_rows, long long rows_per_sample, int K, int F) {
+  if (n_rows <= 0 || rows_per_sample <= 0 || K < kBK || F < 8) return AERIS_ERR_INVALID_SHAPE;
+  if (K % kBK != 0 || F % 8 != 0 || n_rows % rows_per_sample != 0) return AERIS_ERR_NOT_DIVISIBLE;
   if (n_rows / rows_per_sample > 65535) return AERIS_ERR_INVALID_SHAPE;   // a grid dimension
   // 32-bit byte offsets inside a workgroup's operand tiles, 31-bit tile counts
-  if ((long long)features * channels * 2 >= (1LL << 32)) return AERIS_ERR_INVALID_SHAPE;
+  if ((long long)F * K * 2 >= (1LL << 32)) return AERIS_ERR_INVALID_SHAPE;
   const long long m_tiles = (n_rows / rows_per_sample) * ((rows_per_sample + kBM - 1) / kBM);
-  const long long n_tiles = (features + kBN - 1) / kBN;
+  const long long n_tiles = (F + kBN - 1) / kBN;
   if (((m_tiles + 63) / 64) * 64 * n_tiles >= (1LL << 31)) return AERIS_ERR_INVALID_SHAPE;
   return AERIS_OK;
 }
 
+namespace {
+
+int check_projection(int64_t n_rows, int64_t rows_per_sample, int32_t channels, int32_t features) {
+  if (n_rows <= 0 || rows_per_sample <= 0 || channels <= 0 || features <= 0)
+    return AERIS_ERR_INVALID_SHAPE;
+  if (channels > AERIS_MAX_PROJECTION_CHANNELS) return AERIS_ERR_INVALID_SHAPE;
+  return projection_gemm_check(n_rows, rows_per_sample, channels, features);
+}
+
 bool bad16(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15) != 0; }
 
-int launch_gemm(GemmParams p, hipStream_t stream) {
+}  // namespace
+
+int launch_projection_gemm(GemmParams p, hipStream_t stream) {
   p.m_tiles_per_sample = (int)((p.rows_per_sample + kBM - 1) / kBM);
   if (!allow_full_lds<norm_linear_gemm_kernel>()) return -1;
   // two operand stages; the epilogue reuses them as eight 128 x 144-byte staging regions
@@ -368,6 +362,8 @@ int launch_gemm(GemmParams p, hipStream_t stream) {
   return launch_kernel(norm_linear_gemm_kernel, dim3(gemm_grid(p)), dim3(kGemmWaves * 64), kSmem,
                        stream, p);
 }
+
+namespace {
 
 struct Folded {
   bf16_t* w;
@@ -424,7 +420,7 @@ int norm_projection(const void* x, const float* w, const float* gamma, const flo
   p.F = features;
   p.swiglu = swiglu ? 1 : 0;
   p.n_tiles = swiglu ? (features / 2 + kBN / 2 - 1) / (kBN / 2) : (features + kBN - 1) / kBN;
-  return launch_gemm(p, st) == 0 ? AERIS_OK : AERIS_ERR_HIP_LAUNCH;
+  return launch_projection_gemm(p, st) == 0 ? AERIS_OK : AERIS_ERR_HIP_LAUNCH;
 }
 
 }  // namespace
@@ -475,5 +471,5 @@ extern "C" int aeris_linear_fwd(const void* x, const void* weight, int64_t n_row
   p.K = channels;
   p.F = out_features;
   p.n_tiles = (out_features + kBN - 1) / kBN;
-  return launch_gemm(p, static_cast<hipStream_t>(hip_stream)) == 0 ? AERIS_OK : AERIS_ERR_HIP_LAUNCH;
+  return launch_projection_gemm(p, static_cast<hipStream_t>(hip_stream)) == 0 ? AERIS_OK : AERIS_ERR_HIP_LAUNCH;
 }

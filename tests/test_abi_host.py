@@ -253,3 +253,25 @@ def test_projections_reject_bad_arguments_before_launching():
     lin = lambda **kw: lib.aeris_linear_fwd(kw.get("x", a), a, kw.get("n", 512), kw.get("c", 128),
                                             kw.get("f", 384), kw.get("y", a), None)
     assert lin(x=None) == -1 and lin(c=100) == -3 and lin(f=4) == -2 and lin(y=odd) == -7
+
+
+def test_linear_bwd_rejects_bad_arguments_before_launching():
+    lib = B.load()
+    a = ctypes.c_void_p(4096)
+    odd = ctypes.c_void_p(4096 + 8)
+    # 2048 rows, 256 channels, 512 features: 2 output tiles, 32 steps -> 2 row ranges of 16 steps;
+    # transposed weight (512 x 256 bf16) + 2 partial results (512 x 256 fp32)
+    need = lib.aeris_linear_bwd_workspace_bytes(2048, 256, 512)
+    assert need == 512 * 256 * 2 + 2 * 512 * 256 * 4
+    # the headline QKV shape: 192 tiles, 64800 steps in 11 row ranges
+    assert lib.aeris_linear_bwd_workspace_bytes(4 * 720 * 1440, 2048, 6144) == 6144 * 2048 * (2 + 11 * 4)
+    assert lib.aeris_linear_bwd_workspace_bytes(2000, 256, 512) == 0          # 2000 % 64
+    call = lambda **kw: lib.aeris_linear_bwd(
+        kw.get("x", a), kw.get("w", a), kw.get("dy", a), kw.get("n", 2048), kw.get("c", 256),
+        kw.get("f", 512), kw.get("dx", a), kw.get("dw", a), kw.get("wsp", a), kw.get("ws", need), None)
+    assert call(dy=None) == -1 and call(wsp=None) == -1 and call(dx=None, dw=None) == -1
+    assert call(w=None) == -1 and call(x=None) == -1            # needed by the outputs asked for
+    assert call(n=2000) == -3 and call(c=96) == -3 and call(f=520) == -3
+    assert call(n=0) == -2 and call(c=0) == -2
+    assert call(dx=odd) == -7 and call(dy=odd) == -7
+    assert call(ws=need - 1) == -8
