@@ -151,8 +151,8 @@ int aeris_linear_fwd(const void* x, const void* weight, int64_t n_rows, int32_t 
  * contiguous, read only.  Either output may be NULL (then its operand x or weight may be too).
  * dweight is overwritten, not accumulated into; it is the sum of per-row-range partial results
  * added in a fixed order, so it does not depend on the schedule.
- * Limits: channels % 64 == 0, out_features % 64 == 0, n_rows % 64 == 0,
- * out_features * channels < 2^31.  workspace: >= aeris_linear_bwd_workspace_bytes(...) bytes
+ * Limits: channels % 64 == 0, out_features % 64 == 0, out_features * channels < 2^31; any
+ * n_rows >= 1.  workspace: >= aeris_linear_bwd_workspace_bytes(...) bytes
  * (the transposed weight and the partial results), 16-byte aligned, contents undefined before
  * and after.  Errors as elsewhere: AERIS_ERR_ codes, checked before any launch.
  */

@@ -13,7 +13,8 @@
 // with transposing reads (ds_read_b64_tr_b16), the token index landing in the registers.  The
 // row range of the whole problem is split over several workgroups per tile; each writes its
 // partial tile, and a second kernel adds the partials in a fixed order (no atomics: the result
-// does not depend on the schedule).
+// does not depend on the schedule) together with the products of the rows past the last whole
+// step of 64.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -175,16 +176,33 @@ __global__ __launch_bounds__(kWgradWaves * 64, 1) void linear_wgrad_kernel(Wgrad
     }
 }
 
-// dW = sum of the partial tiles, in the order of the splits.  n4: number of 4-float groups.
+// dW = sum of the partial tiles, in the order of the splits, plus the products of the last
+// n_rows % 64 rows (`tail` rows starting at row `row0`), which the tile kernel does not take:
+// at most 63 multiply-adds per element, in row order.  n4: number of 4-float groups of dW.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ part,
                                                            long long n4, int splits,
+                                                           const bf16_t* __restrict__ dy,
+                                                           const bf16_t* __restrict__ x,
+                                                           long long row0, int tail, int F, int C,
                                                            float* __restrict__ dw) {
   const long long stride = (long long)gridDim.x * 256;
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
-    f32x4 s = reinterpret_cast<const f32x4*>(part)[i];
-    for (int k = 1; k < splits; ++k) {
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < splits; ++k) {
       const f32x4 v = reinterpret_cast<const f32x4*>(part)[(long long)k * n4 + i];
       s[0] += v[0]; s[1] += v[1]; s[2] += v[2]; s[3] += v[3];
+    }
+    if (tail) {
+      const long long e = i * 4;
+      const int f = (int)(e / C), c = (int)(e - (long long)f * C);
+      for (int m = 0; m < tail; ++m) {
+        const float d = (float)dy[(row0 + m) * F + f];
+        const bf16x4 xv = *reinterpret_cast<const bf16x4*>(x + (row0 + m) * C + c);
+        s[0] = __builtin_fmaf(d, (float)xv[0], s[0]);
+        s[1] = __builtin_fmaf(d, (float)xv[1], s[1]);
+        s[2] = __builtin_fmaf(d, (float)xv[2], s[2]);
+        s[3] = __builtin_fmaf(d, (float)xv[3], s[3]);
+      }
     }
     reinterpret_cast<f32x4*>(dw)[i] = s;
   }
@@ -225,13 +243,15 @@ Split choose_split(int64_t n_rows, int32_t channels, int32_t features) {
   long long per = (s.steps_total + want - 1) / want;
   per = per < 16 ? 16 : per;
   s.steps_per_split = (int)per;
-  s.splits = (int)((s.steps_total + per - 1) / per);
+  s.splits = (int)((s.steps_total + per - 1) / per);      // 0 if there is no whole step
   return s;
 }
+// whether the tile kernel can write dW itself: one row range and no rows left over
+bool direct_dw(const Split& s, int64_t n_rows) { return s.splits == 1 && n_rows % kTM == 0; }
 
 int check_linear_bwd(int64_t n_rows, int32_t channels, int32_t features) {
   if (n_rows <= 0 || channels <= 0 || features <= 0) return AERIS_ERR_INVALID_SHAPE;
-  if (channels % 64 != 0 || features % 64 != 0 || n_rows % kTM != 0) return AERIS_ERR_NOT_DIVISIBLE;
+  if (channels % 64 != 0 || features % 64 != 0) return AERIS_ERR_NOT_DIVISIBLE;
   if (n_rows / kTM >= (1LL << 31)) return AERIS_ERR_INVALID_SHAPE;
   // dx: the forward kernel with the roles of channels and features exchanged
   if (const int rc = projection_gemm_check(n_rows, n_rows, features, channels)) return rc;
@@ -251,7 +271,7 @@ extern "C" size_t aeris_linear_bwd_workspace_bytes(int64_t n_rows, int32_t chann
   if (check_linear_bwd(n_rows, channels, out_features) != AERIS_OK) return 0;
   const Split s = choose_split(n_rows, channels, out_features);
   return round256((size_t)out_features * channels * 2) +
-         round256((size_t)s.splits * out_features * channels * 4);
+         (direct_dw(s, n_rows) ? 0 : round256((size_t)s.splits * out_features * channels * 4));
 }
 
 extern "C" int aeris_linear_bwd(const void* x, const void* weight, const void* dy, int64_t n_rows,
@@ -290,7 +310,8 @@ extern "C" int aeris_linear_bwd(const void* x, const void* weight, const void* d
     WgradParams p{};
     p.dy = static_cast<const bf16_t*>(dy);
     p.x = static_cast<const bf16_t*>(x);
-    p.out = s.splits == 1 ? dweight : part;
+    const bool direct = direct_dw(s, n_rows);
+    p.out = direct ? dweight : part;
     p.F = out_features;
     p.C = channels;
     p.f_tiles = (out_features + kTF - 1) / kTF;
@@ -299,16 +320,20 @@ extern "C" int aeris_linear_bwd(const void* x, const void* weight, const void* d
     p.splits = s.splits;
     p.steps_per_split = s.steps_per_split;
     p.steps_total = s.steps_total;
-    if (!allow_full_lds<linear_wgrad_kernel>()) return AERIS_ERR_HIP_LAUNCH;
-    if (launch_kernel(linear_wgrad_kernel, dim3(wgrad_grid(p)), dim3(kWgradWaves * 64),
-                      (size_t)2 * kWgradStageBytes, st, p) != 0)
-      return AERIS_ERR_HIP_LAUNCH;
-    if (s.splits > 1) {
+    if (s.splits > 0) {
+      if (!allow_full_lds<linear_wgrad_kernel>()) return AERIS_ERR_HIP_LAUNCH;
+      if (launch_kernel(linear_wgrad_kernel, dim3(wgrad_grid(p)), dim3(kWgradWaves * 64),
+                        (size_t)2 * kWgradStageBytes, st, p) != 0)
+        return AERIS_ERR_HIP_LAUNCH;
+    }
+    if (!direct) {
       const long long n4 = (long long)out_features * channels / 4;
       const long long blocks = (n4 + 255) / 256;
       if (launch_kernel(wgrad_reduce_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)),
                         dim3(256), 0, st, static_cast<const float*>(part), n4, s.splits,
-                        dweight) != 0)
+                        static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(x),
+                        (long long)s.steps_total * kTM, (int)(n_rows % kTM), (int)out_features,
+                        (int)channels, dweight) != 0)
         return AERIS_ERR_HIP_LAUNCH;
     }
   }

@@ -265,13 +265,18 @@ def test_linear_bwd_rejects_bad_arguments_before_launching():
     assert need == 512 * 256 * 2 + 2 * 512 * 256 * 4
     # the headline QKV shape: 192 tiles, 64800 steps in 11 row ranges
     assert lib.aeris_linear_bwd_workspace_bytes(4 * 720 * 1440, 2048, 6144) == 6144 * 2048 * (2 + 11 * 4)
-    assert lib.aeris_linear_bwd_workspace_bytes(2000, 256, 512) == 0          # 2000 % 64
+    # 2000 rows: 31 whole steps in 2 row ranges; the 16 rows left over are added with them
+    assert lib.aeris_linear_bwd_workspace_bytes(2000, 256, 512) == need
+    # one row range and nothing left over: the tile kernel writes dW itself
+    assert lib.aeris_linear_bwd_workspace_bytes(1024, 256, 512) == 512 * 256 * 2
+    assert lib.aeris_linear_bwd_workspace_bytes(1000, 256, 512) == 512 * 256 * 2 + 512 * 256 * 4
+    assert lib.aeris_linear_bwd_workspace_bytes(2048, 256, 520) == 0          # 520 % 64
     call = lambda **kw: lib.aeris_linear_bwd(
         kw.get("x", a), kw.get("w", a), kw.get("dy", a), kw.get("n", 2048), kw.get("c", 256),
         kw.get("f", 512), kw.get("dx", a), kw.get("dw", a), kw.get("wsp", a), kw.get("ws", need), None)
     assert call(dy=None) == -1 and call(wsp=None) == -1 and call(dx=None, dw=None) == -1
     assert call(w=None) == -1 and call(x=None) == -1            # needed by the outputs asked for
-    assert call(n=2000) == -3 and call(c=96) == -3 and call(f=520) == -3
+    assert call(c=96) == -3 and call(f=520) == -3
     assert call(n=0) == -2 and call(c=0) == -2
     assert call(dx=odd) == -7 and call(dy=odd) == -7
     assert call(ws=need - 1) == -8

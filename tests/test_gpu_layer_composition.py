@@ -1,13 +1,14 @@
-"""The attention half of a transformer layer put together from this library's entry points, with
-the two projections done by torch's bf16 matmul (the layer's GEMMs belong to the caller):
+"""The attention half of a transformer layer put together from this library's entry points
+alone, projections included:
 
     h   = RMSNorm(x; w) (1 + gamma) + beta          aeris_rmsnorm_adaln_fwd
-    qkv = h Wqkv^T                                   torch.matmul (bf16), [N, 3C] packed
+    qkv = h Wqkv^T                                   aeris_linear_fwd, [N, 3C] packed
     a   = window attention(rope(q), rope(k), v)      aeris_winattn_rope_fwd on the packed qkv
-    y   = a Wo^T                                     torch.matmul
+    y   = a Wo^T                                     aeris_linear_fwd
     out = x + alpha y                                aeris_gate_residual_fwd
 
-and its backward pass through the matching entry points.  The reference chains the fp64 oracles
+and its backward pass through the matching entry points (aeris_linear_bwd for the gradients of
+both projections).  The reference chains the fp64 oracles
 (oracle/block_oracle.py, oracle/rope_oracle.py) with fp64 matrix products, rounding to bf16
 exactly where the GPU path stores a bf16 tensor (h, qkv, a, y, and the gradients handed from one
 stage to the next), so that both sides feed the same kind of operands to every stage; and,
@@ -98,7 +99,7 @@ def test_attention_half_of_a_layer_forward_and_backward():
     f32 = lambda a_: torch.from_numpy(a_.astype(np.float32)).cuda()
     tw, tgamma, tbeta, talpha = f32(w), f32(gamma), f32(beta), f32(alpha)
     th, tr = B.aeris_rmsnorm_adaln_fwd(tx, tw, tgamma, tbeta, eps, rps)
-    tqkv = torch.matmul(th, twqkv.t()).contiguous()            # [N, 3C] = [B,H,W,3,nh,d]
+    tqkv = B.aeris_linear_fwd(th, twqkv)                       # [N, 3C] = [B,H,W,3,nh,d]
     shape = (Bn, H, W, nh, d)
     p = B.make_params(shape, win, shift, mask, qkv_strides=(3 * C, d))
     r = B.aeris_rope_params(base, mode)
@@ -114,20 +115,18 @@ def test_attention_half_of_a_layer_forward_and_backward():
                                     part(tqkv, 2), ta.data_ptr(), tlse.data_ptr(), fws.data_ptr(),
                                     fws.numel(), stream)
     assert rc == 0
-    ty = torch.matmul(ta, two.t())
+    ty = B.aeris_linear_fwd(ta, two)
     tout = B.aeris_gate_residual_fwd(tx, ty, talpha, rps)
     # backward
     tdy, tdalpha = B.aeris_gate_residual_bwd(ty, talpha, tdout, rps)
-    tdwo = torch.matmul(tdy.t().float(), ta.float())
-    tda = torch.matmul(tdy, two)
+    tda, tdwo = B.aeris_linear_bwd(ta, two, tdy)
     tdqkv = torch.empty_like(tqkv)
     rc = lib.aeris_winattn_rope_bwd(ctypes.byref(p), ctypes.byref(r), part(tqkv, 0), part(tqkv, 1),
                                     part(tqkv, 2), ta.data_ptr(), tlse.data_ptr(), tda.data_ptr(),
                                     part(tdqkv, 0), part(tdqkv, 1), part(tdqkv, 2), fws.data_ptr(),
                                     ws.data_ptr(), ws.numel(), stream)
     assert rc == 0
-    tdwqkv = torch.matmul(tdqkv.t().float(), th.float())
-    tdh = torch.matmul(tdqkv, twqkv)
+    tdh, tdwqkv = B.aeris_linear_bwd(th, twqkv, tdqkv)
     tdxn, tdw, tdgamma, tdbeta = B.aeris_rmsnorm_adaln_bwd(tx, tw, tgamma, tr, tdh, rps)
     tdx = (tdout.float() + tdxn.float())
     torch.cuda.synchronize()
@@ -153,7 +152,9 @@ def test_attention_half_of_a_layer_forward_and_backward():
 
 
 def test_swiglu_half_of_a_layer_forward_and_backward():
-    """out = x + alpha * (swiglu(h Wup^T) Wdown^T),  h = RMSNorm(x; w) (1 + gamma) + beta."""
+    """out = x + alpha * (swiglu(h Wup^T) Wdown^T),  h = RMSNorm(x; w) (1 + gamma) + beta, forward
+    and backward, every step by this library (1500 rows: 28 rows past the last whole step of the
+    weight-gradient kernel)."""
     Bn, rps, C, F = 3, 500, 256, 512
     N = Bn * rps
     eps = 1e-6
@@ -187,16 +188,14 @@ def test_swiglu_half_of_a_layer_forward_and_backward():
     f32 = lambda a_: torch.from_numpy(a_.astype(np.float32)).cuda()
     tw, tgamma, tbeta, talpha = f32(w), f32(gamma), f32(beta), f32(alpha)
     th, tr = B.aeris_rmsnorm_adaln_fwd(tx, tw, tgamma, tbeta, eps, rps)
-    tuv = torch.matmul(th, twup.t())
+    tuv = B.aeris_linear_fwd(th, twup)
     tg = B.aeris_swiglu_fwd(tuv)
-    ty = torch.matmul(tg, twdown.t())
+    ty = B.aeris_linear_fwd(tg, twdown)
     tout = B.aeris_gate_residual_fwd(tx, ty, talpha, rps)
     tdy, tdalpha = B.aeris_gate_residual_bwd(ty, talpha, tdout, rps)
-    tdwdown = torch.matmul(tdy.t().float(), tg.float())
-    tdg = torch.matmul(tdy, twdown)
+    tdg, tdwdown = B.aeris_linear_bwd(tg, twdown, tdy)
     tduv = B.aeris_swiglu_bwd(tuv, tdg)
-    tdwup = torch.matmul(tduv.t().float(), th.float())
-    tdh = torch.matmul(tduv, twup)
+    tdh, tdwup = B.aeris_linear_bwd(th, twup, tduv)
     tdxn, tdw, tdgamma, tdbeta = B.aeris_rmsnorm_adaln_bwd(tx, tw, tgamma, tr, tdh, rps)
     tdx = tdout.float() + tdxn.float()
     torch.cuda.synchronize()

@@ -69,6 +69,9 @@ CASES = [
     (4096, 256, 512),         # two feature tiles, four row ranges added by the second kernel
     (2112, 2048, 448),        # the headline width; 33 steps: the last row range holds one step
     (8256, 128, 6144),        # 24 feature tiles (three per XCD), nine row ranges
+    (1000, 192, 320),         # 15 whole steps and 40 rows left over
+    (40, 64, 128),            # fewer rows than one step: everything is "left over"
+    (4159, 256, 512),         # four row ranges and 63 rows left over
     (1024, 64, 11008),        # the SwiGLU width: 43 feature tiles (empty slots on five XCDs);
                               # dx contracts over 11008 features
 ]
@@ -150,8 +153,8 @@ def test_qkv_projection_backward_at_the_headline_size_on_samples():
 def test_linear_bwd_errors_are_reported():
     bf = lambda *s: torch.zeros(*s, dtype=torch.bfloat16, device="cuda")
     ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
-    with pytest.raises(B.AerisError) as e:                       # 100 rows: not a multiple of 64
-        B.aeris_linear_bwd(bf(100, 64), bf(64, 64), bf(100, 64), workspace=ws)
+    with pytest.raises(B.AerisError) as e:                       # 96 channels: not a multiple of 64
+        B.aeris_linear_bwd(bf(128, 96), bf(64, 96), bf(128, 64), workspace=ws)
     assert e.value.code == -3
     with pytest.raises(B.AerisError) as e:                       # 72 features: not a multiple of 64
         B.aeris_linear_bwd(bf(128, 64), bf(72, 64), bf(128, 72), workspace=ws)
