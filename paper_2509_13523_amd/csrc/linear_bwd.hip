@@ -40,24 +40,31 @@ struct WgradParams {
   const bf16_t* x;             // [M, C]
   float* out;                  // [splits][F, C]
   int F, C;
-  int f_tiles, c_tiles, f_tiles_per_xcd;
+  int f_tiles, c_tiles;
+  int cu, f_groups, c_groups;  // a unit is (32 / cu) x cu tiles
   int splits;
   int steps_per_split, steps_total;      // steps of kTM rows
 };
 
 // Workgroup id -> (split, feature tile, channel tile).  Consecutive ids go to the eight XCDs in
-// turn; an XCD keeps whole rows of channel tiles (they share the dy rows of their feature tile
-// in its L2), and runs the tiles of one split before those of the next.
+// turn.  The 32 workgroups an XCD runs at a time form one unit: fu x cu output tiles of the
+// same row range, so that each 64-row piece of dy or x that arrives in that XCD's L2 serves cu
+// or fu workgroups which walk the rows together.
 __device__ __forceinline__ bool wgrad_tile(const WgradParams& p, int& split, int& ft, int& ct) {
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  ct = slot % p.c_tiles;
-  const int t = slot / p.c_tiles;
-  split = t / p.f_tiles_per_xcd;
-  ft = xcd + 8 * (t - split * p.f_tiles_per_xcd);
-  return ft < p.f_tiles;
+  const int unit = (slot >> 5) * 8 + xcd, t = slot & 31;
+  const int fu = 32 / p.cu;
+  const int cg = unit % p.c_groups;
+  const int rest = unit / p.c_groups;
+  const int fg = rest % p.f_groups;
+  split = rest / p.f_groups;
+  ct = cg * p.cu + t % p.cu;
+  ft = fg * fu + t / p.cu;
+  return split < p.splits && ft < p.f_tiles && ct < p.c_tiles;
 }
 inline unsigned wgrad_grid(const WgradParams& p) {
-  return 8u * (unsigned)p.splits * (unsigned)p.f_tiles_per_xcd * (unsigned)p.c_tiles;
+  const unsigned units = (unsigned)p.splits * (unsigned)p.f_groups * (unsigned)p.c_groups;
+  return ((units + 7) / 8) * 8 * 32;
 }
 
 __global__ __launch_bounds__(kWgradWaves * 64, 1) void linear_wgrad_kernel(WgradParams p) {
@@ -229,21 +236,43 @@ __global__ __launch_bounds__(256) void transpose_weight_kernel(const bf16_t* __r
 size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
 bool bad16(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15) != 0; }
 
-// How the rows are split for dW: enough workgroups to fill the chip several times over, but
-// at least 16 steps each, at most 64 partial tiles per output tile.
+// How the rows are split for dW: enough workgroups to fill the chip several times over, but at
+// least 16 steps each and at most 64 partial tiles per output tile; among the next few counts
+// the one whose units (32 tiles, one XCD's worth) fill the eight XCDs most evenly.
 struct Split {
   int steps_total, steps_per_split, splits;
+  int cu, f_groups, c_groups;
 };
 Split choose_split(int64_t n_rows, int32_t channels, int32_t features) {
   Split s;
   s.steps_total = (int)(n_rows / kTM);
-  const long long tiles = (long long)((features + kTF - 1) / kTF) * ((channels + kTC - 1) / kTC);
+  const int f_tiles = (features + kTF - 1) / kTF, c_tiles = (channels + kTC - 1) / kTC;
+  s.cu = c_tiles >= 8 ? 8 : (c_tiles >= 4 ? 4 : (c_tiles >= 2 ? 2 : 1));
+  s.c_groups = (c_tiles + s.cu - 1) / s.cu;
+  s.f_groups = (f_tiles + 32 / s.cu - 1) / (32 / s.cu);
+  const long long tiles = (long long)f_tiles * c_tiles;
   long long want = (2048 + tiles - 1) / tiles;
   want = want < 1 ? 1 : (want > 64 ? 64 : want);
-  long long per = (s.steps_total + want - 1) / want;
-  per = per < 16 ? 16 : per;
-  s.steps_per_split = (int)per;
-  s.splits = (int)((s.steps_total + per - 1) / per);      // 0 if there is no whole step
+  auto layout = [&](long long target, int& per_out, int& splits_out) {
+    long long per = (s.steps_total + target - 1) / target;
+    per = per < 16 ? 16 : per;
+    per_out = (int)per;
+    splits_out = (int)((s.steps_total + per - 1) / per);    // 0 if there is no whole step
+  };
+  layout(want, s.steps_per_split, s.splits);
+  double best = -1.0;
+  for (long long target = want; target < want + 8 && target <= 64; ++target) {
+    int per, splits;
+    layout(target, per, splits);
+    if (splits == 0) break;
+    const long long units = (long long)splits * s.f_groups * s.c_groups;
+    const double fill = (double)units / (double)(((units + 7) / 8) * 8);
+    if (fill > best + 1e-9) {
+      best = fill;
+      s.steps_per_split = per;
+      s.splits = splits;
+    }
+  }
   return s;
 }
 // whether the tile kernel can write dW itself: one row range and no rows left over
@@ -316,7 +345,9 @@ extern "C" int aeris_linear_bwd(const void* x, const void* weight, const void* d
     p.C = channels;
     p.f_tiles = (out_features + kTF - 1) / kTF;
     p.c_tiles = (channels + kTC - 1) / kTC;
-    p.f_tiles_per_xcd = (p.f_tiles + 7) / 8;
+    p.cu = s.cu;
+    p.c_groups = s.c_groups;
+    p.f_groups = s.f_groups;
     p.splits = s.splits;
     p.steps_per_split = s.steps_per_split;
     p.steps_total = s.steps_total;

@@ -263,8 +263,9 @@ def test_linear_bwd_rejects_bad_arguments_before_launching():
     # transposed weight (512 x 256 bf16) + 2 partial results (512 x 256 fp32)
     need = lib.aeris_linear_bwd_workspace_bytes(2048, 256, 512)
     assert need == 512 * 256 * 2 + 2 * 512 * 256 * 4
-    # the headline QKV shape: 192 tiles, 64800 steps in 11 row ranges
-    assert lib.aeris_linear_bwd_workspace_bytes(4 * 720 * 1440, 2048, 6144) == 6144 * 2048 * (2 + 11 * 4)
+    # the headline QKV shape: 192 tiles in 6 units of 32; 64800 steps in 12 row ranges (72 units:
+    # nine for each XCD)
+    assert lib.aeris_linear_bwd_workspace_bytes(4 * 720 * 1440, 2048, 6144) == 6144 * 2048 * (2 + 12 * 4)
     # 2000 rows: 31 whole steps in 2 row ranges; the 16 rows left over are added with them
     assert lib.aeris_linear_bwd_workspace_bytes(2000, 256, 512) == need
     # one row range and nothing left over: the tile kernel writes dW itself
