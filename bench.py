@@ -120,12 +120,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS) + ["layer_ops", "qkv_proj", "qkv_proj_bwd"],
+    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS) + ["layer_ops", "qkv_proj", "qkv_proj_bwd", "layer"],
                     help="layer_ops: the element-wise kernels of include/aeris_layer_ops.h on the "
                          "headline grid's tokens (a bandwidth figure, not the headline metric); "
                          "qkv_proj: the fused RMSNorm + modulation + QKV projection and the fused "
                          "SwiGLU up-projection on the same tokens (bf16 MFMA TFLOP/s); "
-                         "qkv_proj_bwd: the two gradient GEMMs of the QKV projection")
+                         "qkv_proj_bwd: the two gradient GEMMs of the QKV projection; "
+                         "layer: one whole transformer layer, forward and backward, on one "
+                         "sample of the headline grid, every step by this library")
     ap.add_argument("--channels", type=int, default=2048, help="row width for --workload layer_ops")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-pairs", type=int, default=64)
@@ -153,6 +155,8 @@ def main():
         return bench_projections(args)
     if args.workload == "qkv_proj_bwd":
         return bench_projection_bwd(args)
+    if args.workload == "layer":
+        return bench_layer(args)
     wl = WORKLOADS[args.workload]
     shape, win, mask = wl["shape"], wl["win"], wl["mask"]
     Bn, H, W, nh, d = shape
@@ -539,6 +543,134 @@ def bench_projection_bwd(args):
                                             else "norm_linear_gemm_kernel", slow), "bound": "mfma",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None}}))
+
+
+def bench_layer(args):
+    """One step = one AERIS transformer layer (Model Architecture section: adaptive RMSNorm ->
+    QKV projection -> rotary shifted-window attention -> output projection -> gated residual;
+    adaptive RMSNorm -> SwiGLU feed-forward -> gated residual), forward and backward, on ONE
+    sample of the headline grid (720 x 1440 tokens, 2048 channels = 16 heads x 128, 60 x 60
+    windows shifted by 30, SWIN mask, hidden width 5504), every step an entry point of this
+    library; the two residual sums of the backward pass are torch adds.  FLOPs: the GEMMs
+    (2 N C F each forward, twice that backward) plus the attention's model FLOPs."""
+    import ctypes
+    import torch
+    from paper_2509_13523_amd import binding as B
+    H, W, nh, d, hidden = 720, 1440, 16, 128, 5504
+    C, N, rps = nh * d, H * W, H * W
+    win, shift, mask, base, eps = (60, 60), (30, 30), B.AERIS_MASK_SWIN, 100.0, 1e-6
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    gen = torch.Generator(device=dev).manual_seed(7300)
+    bf = lambda *sh, scale=1.0: (torch.randn(*sh, device=dev, generator=gen) * scale).to(torch.bfloat16)
+    f32 = lambda *sh, scale=1.0, shift_=0.0: shift_ + scale * torch.randn(*sh, device=dev, generator=gen)
+    x, dout = bf(N, C), bf(N, C)
+    wqkv, wo = bf(3 * C, C, scale=C ** -0.5), bf(C, C, scale=C ** -0.5)
+    wup, wdown = bf(2 * hidden, C, scale=C ** -0.5), bf(C, hidden, scale=hidden ** -0.5)
+    w1, w2 = f32(C, scale=0.1, shift_=1.0), f32(C, scale=0.1, shift_=1.0)
+    g1, b1, a1 = f32(1, C, scale=0.3), f32(1, C, scale=0.5), f32(1, C, scale=0.8)
+    g2, b2, a2 = f32(1, C, scale=0.3), f32(1, C, scale=0.5), f32(1, C, scale=0.8)
+    lib = B.load()
+    p = B.make_params((1, H, W, nh, d), win, shift, mask, qkv_strides=(3 * C, d))
+    rp = B.aeris_rope_params(base, B.AERIS_ROPE_POS_WINDOW)
+    u8 = lambda nbytes: torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=dev)
+    ws_proj = u8(B.aeris_norm_linear_workspace_bytes(N, rps, C, 2 * hidden))
+    ws_attn_f = u8(B.aeris_winattn_rope_fwd_workspace_bytes(p))
+    ws_attn_b = u8(B.aeris_winattn_bwd_workspace_bytes(p))
+    ws_lin = u8(max(B.aeris_linear_bwd_workspace_bytes(N, C, 2 * hidden),
+                    B.aeris_linear_bwd_workspace_bytes(N, hidden, C),
+                    B.aeris_linear_bwd_workspace_bytes(N, C, 3 * C)))
+    ws_el = u8(max(B.aeris_rmsnorm_adaln_bwd_workspace_bytes(N, rps, C),
+                   B.aeris_gate_residual_bwd_workspace_bytes(N, rps, C)))
+    lse = torch.empty(1, nh, H, W, dtype=torch.float32, device=dev)
+    a = torch.empty(N, C, dtype=torch.bfloat16, device=dev)
+    dqkv = torch.empty(N, 3 * C, dtype=torch.bfloat16, device=dev)
+    part = lambda t, i: t.data_ptr() + i * C * 2
+    log = []
+
+    def op(name, fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        out = fn()
+        e1.record()
+        log.append((name, e0, e1))
+        return out
+
+    def attn_fwd(qkv):
+        rc = lib.aeris_winattn_rope_fwd(ctypes.byref(p), ctypes.byref(rp), part(qkv, 0), part(qkv, 1),
+                                        part(qkv, 2), a.data_ptr(), lse.data_ptr(), ws_attn_f.data_ptr(),
+                                        ws_attn_f.numel(), torch.cuda.current_stream().cuda_stream)
+        assert rc == 0, rc
+
+    def attn_bwd(qkv, da):
+        rc = lib.aeris_winattn_rope_bwd(ctypes.byref(p), ctypes.byref(rp), part(qkv, 0), part(qkv, 1),
+                                        part(qkv, 2), a.data_ptr(), lse.data_ptr(), da.data_ptr(),
+                                        part(dqkv, 0), part(dqkv, 1), part(dqkv, 2), ws_attn_f.data_ptr(),
+                                        ws_attn_b.data_ptr(), ws_attn_b.numel(),
+                                        torch.cuda.current_stream().cuda_stream)
+        assert rc == 0, rc
+
+    def step():
+        # ---- forward
+        qkv = op("norm_qkv_projection", lambda: B.aeris_norm_linear_fwd(x, w1, g1, b1, eps, wqkv, rps, workspace=ws_proj))
+        op("attention_fwd", lambda: attn_fwd(qkv))
+        y = op("out_projection", lambda: B.aeris_linear_fwd(a, wo))
+        x1 = op("gate_residual_fwd", lambda: B.aeris_gate_residual_fwd(x, y, a1, rps))
+        g, uv = op("norm_swiglu_up_projection", lambda: B.aeris_norm_linear_swiglu_fwd(
+            x1, w2, g2, b2, eps, wup, rps, workspace=ws_proj))
+        y2 = op("down_projection", lambda: B.aeris_linear_fwd(g, wdown))
+        out = op("gate_residual_fwd", lambda: B.aeris_gate_residual_fwd(x1, y2, a2, rps))
+        # ---- backward
+        dy2, _ = op("gate_residual_bwd", lambda: B.aeris_gate_residual_bwd(y2, a2, dout, rps, workspace=ws_el))
+        dg, dwdown = op("down_projection_bwd", lambda: B.aeris_linear_bwd(g, wdown, dy2, workspace=ws_lin))
+        duv = op("swiglu_bwd", lambda: B.aeris_swiglu_bwd(uv, dg))
+        h2, r2 = op("rmsnorm_adaln_fwd (recomputed)", lambda: B.aeris_rmsnorm_adaln_fwd(x1, w2, g2, b2, eps, rps))
+        dh2, dwup = op("up_projection_bwd", lambda: B.aeris_linear_bwd(h2, wup, duv, workspace=ws_lin))
+        dx1n = op("rmsnorm_adaln_bwd", lambda: B.aeris_rmsnorm_adaln_bwd(x1, w2, g2, r2, dh2, rps, workspace=ws_el))[0]
+        dx1 = op("residual_sum (torch)", lambda: torch.add(dout, dx1n))
+        dy, _ = op("gate_residual_bwd", lambda: B.aeris_gate_residual_bwd(y, a1, dx1, rps, workspace=ws_el))
+        da, dwo = op("out_projection_bwd", lambda: B.aeris_linear_bwd(a, wo, dy, workspace=ws_lin))
+        op("attention_bwd", lambda: attn_bwd(qkv, da))
+        h1, r1 = op("rmsnorm_adaln_fwd (recomputed)", lambda: B.aeris_rmsnorm_adaln_fwd(x, w1, g1, b1, eps, rps))
+        dh1, dwqkv = op("qkv_projection_bwd", lambda: B.aeris_linear_bwd(h1, wqkv, dqkv, workspace=ws_lin))
+        dxn = op("rmsnorm_adaln_bwd", lambda: B.aeris_rmsnorm_adaln_bwd(x, w1, g1, r1, dh1, rps, workspace=ws_el))[0]
+        dx = op("residual_sum (torch)", lambda: torch.add(dx1, dxn))
+        return out, dx
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    log.clear()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        out, dx = step()
+    torch.cuda.synchronize()
+    step_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    assert bool(torch.isfinite(out.float()).all()) and bool(torch.isfinite(dx.float()).all())
+    per = {}
+    for name, e0, e1 in log:
+        per[name] = per.get(name, 0.0) + e0.elapsed_time(e1) / args.steps
+    gemm_fl = 3 * 2.0 * N * C * (3 * C + C + 2 * hidden + hidden)
+    attn_fl = 12.0 * d * nh * unmasked_pairs(H, W, win, shift, mask)
+    groups = {"attention": ("attention_fwd", "attention_bwd"),
+              "projections": tuple(k for k in per if "projection" in k),
+              "element-wise": tuple(k for k in per if "projection" not in k and "attention" not in k)}
+    print(json.dumps({
+        "metric": "layer_fwd_bwd_tflops", "value": round((gemm_fl + attn_fl) / (step_ms * 1e-3) / 1e12, 1),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "layer: one transformer layer forward+backward, 1 x %d x %d tokens, %d channels "
+                               "(%d heads x %d), windows %dx%d shifted by %d, SWIN mask, rotary, SwiGLU hidden %d"
+                               % (H, W, C, nh, d, win[0], win[1], shift[0], hidden),
+                   "gemm_tflop": round(gemm_fl / 1e12, 2), "attention_model_tflop": round(attn_fl / 1e12, 2),
+                   "ms": {k: round(v, 3) for k, v in per.items()},
+                   "ms_by_kind": {k: round(sum(per[n] for n in names), 3) for k, names in groups.items()}},
+        "roofline": {"kernel": "whole layer (GEMMs and attention products)", "bound": "mfma",
+                     "achieved": round((gemm_fl + attn_fl) / (step_ms * 1e-3) / 1e12, 1),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round((gemm_fl + attn_fl) / (step_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None}}))
 
 
 def bench_layer_ops(args):
