@@ -68,6 +68,56 @@ LAYER_OPS_TRAFFIC = {"rmsnorm_adaln_fwd": 34.09e9, "rmsnorm_adaln_bwd": 51.04e9,
                      "swiglu_fwd": 25.48e9, "swiglu_bwd": 42.47e9}
 
 
+class PowerSampler:
+    """Board power while a region runs: a thread reads the amdgpu hwmon power file of the first
+    card every 50 ms.  summary() is None if the file is not there (nothing else depends on it)."""
+
+    def __init__(self):
+        import glob
+        self.path = self.cap = None
+        for h in sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*")):
+            for name in ("power1_input", "power1_average"):
+                if os.path.exists(os.path.join(h, name)):
+                    self.path = os.path.join(h, name)
+                    self.cap = os.path.join(h, "power1_cap")
+                    break
+            if self.path:
+                break
+        self.samples, self._stop, self._thread = [], False, None
+
+    def _run(self):
+        while not self._stop:
+            try:
+                self.samples.append(float(open(self.path).read()) / 1e6)
+            except (OSError, ValueError):
+                pass
+            time.sleep(0.05)
+
+    def start(self):
+        if self.path:
+            import threading
+            self.samples, self._stop = [], False
+            self._thread = threading.Thread(target=self._run, daemon=True)
+            self._thread.start()
+        return self
+
+    def summary(self):
+        if not self._thread:
+            return None
+        self._stop = True
+        self._thread.join()
+        xs = sorted(self.samples)
+        if not xs:
+            return None
+        out = {"median_w": round(xs[len(xs) // 2], 0), "max_w": round(xs[-1], 0), "samples": len(xs),
+               "source": "amdgpu hwmon %s, every 50 ms during the timed steps" % os.path.basename(self.path)}
+        try:
+            out["cap_w"] = round(float(open(self.cap).read()) / 1e6, 0)
+        except (OSError, ValueError):
+            pass
+        return out
+
+
 def kernel_symbol(stage, head_dim):
     """Name of the kernel the library launches for a stage (its dispatch rule: the dK/dV stage
     has a software-pipelined kernel of its own at head_dim 128)."""
@@ -239,6 +289,7 @@ def main():
         step(False)
     torch.cuda.synchronize()
     step_marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    power = PowerSampler().start()
     t0 = time.perf_counter()
     step_marks[0].record()
     for i in range(args.steps):
@@ -246,6 +297,7 @@ def main():
         step_marks[i + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    board_power = power.summary()
     ms_per_step = elapsed * 1e3 / args.steps
     value = model_flops / (ms_per_step * 1e-3) / 1e12
     step_ms = sorted(a.elapsed_time(b) for a, b in zip(step_marks, step_marks[1:]))
@@ -312,6 +364,7 @@ def main():
                       "model_tflop_per_step": round(model_flops / 1e12, 2)},
            "kernels": kern, "roofline": roofline}
     out.update(extra)
+    out["board_power"] = board_power
     # algorithmic HBM bytes per step: fwd reads Q,K,V and writes O, LSE; bwd reads Q,K,V,O,dO
     # twice over its three kernels (O,dO; Q,K,V,dO; Q,K,V,dO) and writes dQ,dK,dV
     tensor = 2.0 * Bn * H * W * nh * d
@@ -328,12 +381,15 @@ def main():
         B.aeris_mfma_loop_probe(512, 20000, True, sink)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        loop_power = PowerSampler().start()
         e0.record()
         flop = B.aeris_mfma_loop_probe(512, 600000, True, sink)
         e1.record()
         torch.cuda.synchronize()
         loop_tflops = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        loop_power = loop_power.summary()
         out["roofline"]["measured_mfma_loop_tflops"] = round(loop_tflops, 1)
+        out["roofline"]["measured_mfma_loop_board_power_w"] = loop_power and loop_power["median_w"]
         out["roofline"]["frac_of_measured_loop"] = round(achieved / loop_tflops, 4)
         del sink
 
@@ -424,6 +480,7 @@ def bench_projections(args):
             fn()
     torch.cuda.synchronize()
     ev = {name: [] for name, _, _ in ops}
+    power = PowerSampler().start()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         for name, fn, _ in ops:
@@ -434,6 +491,7 @@ def bench_projections(args):
             ev[name].append((e0, e1))
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    board_power = power.summary()
     step_ms = wall * 1e3 / args.steps
     per = {}
     for name, _, fl in ops:
@@ -457,7 +515,7 @@ def bench_projections(args):
         "metric": "fused_projection_tflops", "value": round(total / (step_ms * 1e-3) / 1e12, 1),
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "board_power": board_power,
         "config": {"workload": "qkv_proj: %d x %d token rows, %d channels -> %d (QKV) and 2 x %d "
                                "(SwiGLU up, gated)" % (nb, rps, C, F, hidden), "kernels": per,
                    "vendor_gemm_qkv_shape_ms": round(vendor_ms, 3),
@@ -508,6 +566,7 @@ def bench_projection_bwd(args):
         for _, fn in ops:
             fn()
     torch.cuda.synchronize()
+    power = PowerSampler().start()
     t0 = time.perf_counter()
     ev = {name: [] for name, _ in ops}
     for _ in range(args.steps):
@@ -519,6 +578,7 @@ def bench_projection_bwd(args):
             ev[name].append((e0, e1))
     torch.cuda.synchronize()
     step_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    board_power = power.summary()
     per = {}
     for name, _ in ops:
         ts = sorted(a.elapsed_time(b) for a, b in ev[name])
@@ -535,7 +595,7 @@ def bench_projection_bwd(args):
         "metric": "projection_backward_tflops", "value": round(2 * fl / (step_ms * 1e-3) / 1e12, 1),
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "board_power": board_power,
         "config": {"workload": "qkv_proj_bwd: %d token rows, %d channels, %d features: dx = dy W "
                                "(bf16) and dW = dy^T x (fp32)" % (n, C, F), "kernels": per,
                    "vendor_gemm_same_products": ven},
@@ -641,11 +701,13 @@ def bench_layer(args):
         step()
     torch.cuda.synchronize()
     log.clear()
+    power = PowerSampler().start()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         out, dx = step()
     torch.cuda.synchronize()
     step_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    board_power = power.summary()
     assert bool(torch.isfinite(out.float()).all()) and bool(torch.isfinite(dx.float()).all())
     per = {}
     for name, e0, e1 in log:
@@ -659,7 +721,7 @@ def bench_layer(args):
         "metric": "layer_fwd_bwd_tflops", "value": round((gemm_fl + attn_fl) / (step_ms * 1e-3) / 1e12, 1),
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(step_ms, 3), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic", "board_power": board_power,
         "config": {"workload": "layer: one transformer layer forward+backward, 1 x %d x %d tokens, %d channels "
                                "(%d heads x %d), windows %dx%d shifted by %d, SWIN mask, rotary, SwiGLU hidden %d"
                                % (H, W, C, nh, d, win[0], win[1], shift[0], hidden),
