@@ -126,18 +126,18 @@ def kernel_symbol(stage, head_dim):
     return "winattn_%s_kernel" % stage
 
 
-def profiled_traffic(workload, stage):
+def profiled_traffic(workload, stage, summary="c5_kernels_and_counters.txt"):
     """HBM bytes per launch of a kernel as the committed rocprofv3 counter summary records them
     (lines `TRAFFIC <workload> <stage> <bytes>` in profiles/): measured in that profiling
     session, not in this run, and labelled so.  None when no summary covers the kernel."""
-    path = os.path.join(ROOT, "profiles", "c5_kernels_and_counters.txt")
+    path = os.path.join(ROOT, "profiles", summary)
     try:
         for line in open(path):
             f = line.split()
             if len(f) == 4 and f[0] == "TRAFFIC" and f[1] == workload and f[2] == stage:
                 return {"traffic": float(f[3]),
-                        "traffic_source": "profiles/c5_kernels_and_counters.txt (rocprofv3 --pmc "
-                                          "FETCH_SIZE + WRITE_SIZE of an earlier run of this file)"}
+                        "traffic_source": "profiles/%s (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE "
+                                          "of an earlier run of this file)" % summary}
     except OSError:
         pass
     return {"traffic": None}
@@ -522,7 +522,9 @@ def bench_projections(args):
                    "vendor_gemm_qkv_shape_tflops": round(2.0 * n * C * F / (vendor_ms * 1e-3) / 1e12, 1)},
         "roofline": {"kernel": "norm_linear_gemm_kernel (%s)" % slow[0], "bound": "mfma",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None}}))
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     **profiled_traffic("qkv_proj", slow[0],
+                                        "projection_gemm_kernel_trace_and_counters.txt")}}))
 
 
 def bench_projection_bwd(args):
@@ -602,7 +604,9 @@ def bench_projection_bwd(args):
         "roofline": {"kernel": "%s (%s)" % ("linear_wgrad_kernel" if slow == "dweight"
                                             else "norm_linear_gemm_kernel", slow), "bound": "mfma",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None}}))
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     **profiled_traffic("qkv_proj_bwd", slow,
+                                        "projection_gemm_kernel_trace_and_counters.txt")}}))
 
 
 def bench_layer(args):
