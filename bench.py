@@ -615,7 +615,8 @@ def bench_layer(args):
     adaptive RMSNorm -> SwiGLU feed-forward -> gated residual), forward and backward, on ONE
     sample of the headline grid (720 x 1440 tokens, 2048 channels = 16 heads x 128, 60 x 60
     windows shifted by 30, SWIN mask, hidden width 5504), every step an entry point of this
-    library; the two residual sums of the backward pass are torch adds.  FLOPs: the GEMMs
+    library (the residual sums of the backward pass are taken inside the RMSNorm backward
+    kernel).  FLOPs: the GEMMs
     (2 N C F each forward, twice that backward) plus the attention's model FLOPs."""
     import ctypes
     import torch
@@ -690,15 +691,15 @@ def bench_layer(args):
         duv = op("swiglu_bwd", lambda: B.aeris_swiglu_bwd(uv, dg))
         h2, r2 = op("rmsnorm_adaln_fwd (recomputed)", lambda: B.aeris_rmsnorm_adaln_fwd(x1, w2, g2, b2, eps, rps))
         dh2, dwup = op("up_projection_bwd", lambda: B.aeris_linear_bwd(h2, wup, duv, workspace=ws_lin))
-        dx1n = op("rmsnorm_adaln_bwd", lambda: B.aeris_rmsnorm_adaln_bwd(x1, w2, g2, r2, dh2, rps, workspace=ws_el))[0]
-        dx1 = op("residual_sum (torch)", lambda: torch.add(dout, dx1n))
+        dx1 = op("rmsnorm_adaln_bwd", lambda: B.aeris_rmsnorm_adaln_bwd(x1, w2, g2, r2, dh2, rps, workspace=ws_el,
+                                                                        dres=dout))[0]
         dy, _ = op("gate_residual_bwd", lambda: B.aeris_gate_residual_bwd(y, a1, dx1, rps, workspace=ws_el))
         da, dwo = op("out_projection_bwd", lambda: B.aeris_linear_bwd(a, wo, dy, workspace=ws_lin))
         op("attention_bwd", lambda: attn_bwd(qkv, da))
         h1, r1 = op("rmsnorm_adaln_fwd (recomputed)", lambda: B.aeris_rmsnorm_adaln_fwd(x, w1, g1, b1, eps, rps))
         dh1, dwqkv = op("qkv_projection_bwd", lambda: B.aeris_linear_bwd(h1, wqkv, dqkv, workspace=ws_lin))
-        dxn = op("rmsnorm_adaln_bwd", lambda: B.aeris_rmsnorm_adaln_bwd(x, w1, g1, r1, dh1, rps, workspace=ws_el))[0]
-        dx = op("residual_sum (torch)", lambda: torch.add(dx1, dxn))
+        dx = op("rmsnorm_adaln_bwd", lambda: B.aeris_rmsnorm_adaln_bwd(x, w1, g1, r1, dh1, rps, workspace=ws_el,
+                                                                       dres=dx1))[0]
         return out, dx
 
     for _ in range(args.warmup):

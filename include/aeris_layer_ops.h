@@ -64,6 +64,19 @@ int aeris_rmsnorm_adaln_bwd(const void* x, const float* w, const float* gamma, c
                             const void* dh, int64_t n_rows, int64_t rows_per_sample,
                             int32_t channels, void* dx, float* dw, float* dgamma, float* dbeta,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
+/*
+ * The same with the residual connection around the normalised branch closed in the same pass
+ * (a layer computes x + branch(RMSNorm(x)), so x receives the branch's gradient plus the
+ * gradient dres [n_rows, channels] bf16 that arrives along the residual path):
+ *     dx = dres + r (dn - n mean_c(dn n))
+ * summed in fp32 and rounded to bf16 once.  dres may be NULL (then this is the call above); it
+ * must not overlap dx.
+ */
+int aeris_rmsnorm_adaln_bwd_residual(const void* x, const float* w, const float* gamma,
+                                     const float* r, const void* dh, const void* dres,
+                                     int64_t n_rows, int64_t rows_per_sample, int32_t channels,
+                                     void* dx, float* dw, float* dgamma, float* dbeta,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Gated residual connection (Model Architecture: alpha of the adaptive layer norm gates the

@@ -85,6 +85,13 @@ def rmsnorm_adaln_bwd(x, w, gamma, beta, eps, rows_per_sample, dh):
     return dx, dw, dgamma, dbeta
 
 
+def rmsnorm_adaln_bwd_residual(x, w, gamma, beta, eps, rows_per_sample, dh, dres):
+    """The same for a layer out = x + branch(h(x)): x also receives the gradient dres that
+    arrives along the residual path (the chain rule adds the two paths)."""
+    dx, dw, dgamma, dbeta = rmsnorm_adaln_bwd(x, w, gamma, beta, eps, rows_per_sample, dh)
+    return dx + np.asarray(dres, dtype=np.float64), dw, dgamma, dbeta
+
+
 def gate_residual_fwd(x, y, alpha, rows_per_sample):
     """out = x + alpha_b * y."""
     x = np.asarray(x, dtype=np.float64)

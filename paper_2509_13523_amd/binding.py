@@ -26,7 +26,7 @@ EXPORTS = ("aeris_winattn_fwd", "aeris_winattn_bwd", "aeris_winattn_bwd_stages",
            "aeris_winattn_rope_bwd_windows",
            # include/aeris_layer_ops.h
            "aeris_rmsnorm_adaln_fwd", "aeris_rmsnorm_adaln_bwd_workspace_bytes",
-           "aeris_rmsnorm_adaln_bwd", "aeris_gate_residual_fwd",
+           "aeris_rmsnorm_adaln_bwd", "aeris_rmsnorm_adaln_bwd_residual", "aeris_gate_residual_fwd",
            "aeris_gate_residual_bwd_workspace_bytes", "aeris_gate_residual_bwd",
            "aeris_swiglu_fwd", "aeris_swiglu_bwd", "aeris_norm_linear_workspace_bytes",
            "aeris_norm_linear_fwd", "aeris_norm_linear_swiglu_fwd", "aeris_linear_fwd",
@@ -120,6 +120,9 @@ def load():
     lib.aeris_rmsnorm_adaln_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, vp, vp, vp, vp,
                                             vp, sz, vp]
     lib.aeris_rmsnorm_adaln_bwd.restype = ctypes.c_int
+    lib.aeris_rmsnorm_adaln_bwd_residual.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i32, vp, vp,
+                                                     vp, vp, vp, sz, vp]
+    lib.aeris_rmsnorm_adaln_bwd_residual.restype = ctypes.c_int
     lib.aeris_gate_residual_fwd.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp]
     lib.aeris_gate_residual_fwd.restype = ctypes.c_int
     lib.aeris_gate_residual_bwd_workspace_bytes.argtypes = [i64, i64, i32]
@@ -479,11 +482,12 @@ def aeris_rmsnorm_adaln_bwd_workspace_bytes(n_rows, rows_per_sample, channels):
 
 
 def aeris_rmsnorm_adaln_bwd(x, w, gamma, r, dh, rows_per_sample, workspace=None,
-                            want=(True, True, True)):
-    """Returns (dx, dw, dgamma, dbeta); entries of `want` switch dw, dgamma, dbeta off (None)."""
+                            want=(True, True, True), dres=None):
+    """Returns (dx, dw, dgamma, dbeta); entries of `want` switch dw, dgamma, dbeta off (None).
+    dres: the gradient arriving along the residual path, added into dx in the same pass."""
     import torch
     n, c = _rows(x)
-    assert _rows(dh) == (n, c)
+    assert _rows(dh) == (n, c) and (dres is None or _rows(dres) == (n, c))
     _f32(w, gamma, r)
     nb = n // rows_per_sample
     dx = torch.empty_like(x)
@@ -493,10 +497,11 @@ def aeris_rmsnorm_adaln_bwd(x, w, gamma, r, dh, rows_per_sample, workspace=None,
     if workspace is None:
         need = aeris_rmsnorm_adaln_bwd_workspace_bytes(n, rows_per_sample, c)
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
-    rc = load().aeris_rmsnorm_adaln_bwd(x.data_ptr(), w.data_ptr(), gamma.data_ptr(),
-                                        r.data_ptr(), dh.data_ptr(), n, rows_per_sample, c,
-                                        dx.data_ptr(), _ptr(dw), _ptr(dgamma), _ptr(dbeta),
-                                        workspace.data_ptr(), workspace.numel(), _stream())
+    rc = load().aeris_rmsnorm_adaln_bwd_residual(x.data_ptr(), w.data_ptr(), gamma.data_ptr(),
+                                                 r.data_ptr(), dh.data_ptr(), _ptr(dres), n,
+                                                 rows_per_sample, c, dx.data_ptr(), _ptr(dw),
+                                                 _ptr(dgamma), _ptr(dbeta), workspace.data_ptr(),
+                                                 workspace.numel(), _stream())
     if rc != 0:
         raise AerisError(rc, "aeris_rmsnorm_adaln_bwd")
     return dx, dw, dgamma, dbeta

@@ -172,7 +172,8 @@ template <int K>
 __global__ __launch_bounds__(kRowThreads) void rmsnorm_adaln_bwd_kernel(
     RowWork rw, const bf16_t* __restrict__ x, const float* __restrict__ w,
     const float* __restrict__ gamma, const float* __restrict__ rstd,
-    const bf16_t* __restrict__ dh, bf16_t* __restrict__ dx, float* __restrict__ partial) {
+    const bf16_t* __restrict__ dh, const bf16_t* __restrict__ dres, bf16_t* __restrict__ dx,
+    float* __restrict__ partial) {
   extern __shared__ __align__(16) float lds_f[];
   float* s_lds = lds_f;
   float* red = lds_f + rw.C;
@@ -196,13 +197,16 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_adaln_bwd_kernel(
   for (int64_t row = r0 + wave; row < r1; row += kRowWaves) {
     const u32x4* xs = reinterpret_cast<const u32x4*>(x + row * C);
     const u32x4* gs = reinterpret_cast<const u32x4*>(dh + row * C);
-    u32x4 xr[K], gr[K];
+    u32x4 xr[K], gr[K], rr[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       const int v = k * 64 + lane;
       const bool in = v * 8 < C;
       xr[k] = in ? __builtin_nontemporal_load(&xs[v]) : u32x4{0, 0, 0, 0};
       gr[k] = in ? __builtin_nontemporal_load(&gs[v]) : u32x4{0, 0, 0, 0};
+      // the gradient that reaches x along the residual path, added before the one rounding
+      rr[k] = (in && dres) ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(dres + row * C) + v)
+                           : u32x4{0, 0, 0, 0};
     }
     const float r = rstd[row];
     float dot = 0.f;
@@ -233,16 +237,17 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_adaln_bwd_kernel(
     for (int k = 0; k < K; ++k) {
       const int v = k * 64 + lane;
       if (v * 8 < C) {
-        float xf[8], gf[8], o[8];
+        float xf[8], gf[8], rf[8], o[8];
         unpack8(xr[k], xf);
         unpack8(gr[k], gf);
+        unpack8(rr[k], rf);
         const f32x4 s0 = *reinterpret_cast<const f32x4*>(s_lds + v * 8);
         const f32x4 s1 = *reinterpret_cast<const f32x4*>(s_lds + v * 8 + 4);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const float n = xf[i] * r;
           const float dn = gf[i] * (i < 4 ? s0[i & 3] : s1[i & 3]);
-          o[i] = r * __builtin_fmaf(-n, m, dn);
+          o[i] = __builtin_fmaf(r, __builtin_fmaf(-n, m, dn), rf[i]);
         }
         __builtin_nontemporal_store(pack8(o), &dst[v]);
       }
@@ -515,9 +520,20 @@ extern "C" int aeris_rmsnorm_adaln_bwd(const void* x, const float* w, const floa
                                        int64_t rows_per_sample, int32_t channels, void* dx,
                                        float* dw, float* dgamma, float* dbeta, void* workspace,
                                        size_t workspace_bytes, void* hip_stream) {
+  return aeris_rmsnorm_adaln_bwd_residual(x, w, gamma, r, dh, nullptr, n_rows, rows_per_sample,
+                                          channels, dx, dw, dgamma, dbeta, workspace,
+                                          workspace_bytes, hip_stream);
+}
+
+extern "C" int aeris_rmsnorm_adaln_bwd_residual(const void* x, const float* w, const float* gamma,
+                                                const float* r, const void* dh, const void* dres,
+                                                int64_t n_rows, int64_t rows_per_sample,
+                                                int32_t channels, void* dx, float* dw,
+                                                float* dgamma, float* dbeta, void* workspace,
+                                                size_t workspace_bytes, void* hip_stream) {
   if (!x || !w || !gamma || !r || !dh || !dx || !workspace) return AERIS_ERR_NULL_POINTER;
   if (const int rc = check_rows(n_rows, rows_per_sample, channels)) return rc;
-  if (bad_ptr(x) || bad_ptr(dh) || bad_ptr(dx) || bad_ptr(w) || bad_ptr(gamma) ||
+  if (bad_ptr(x) || bad_ptr(dh) || bad_ptr(dres) || bad_ptr(dx) || bad_ptr(w) || bad_ptr(gamma) ||
       bad_ptr(workspace) || (reinterpret_cast<uintptr_t>(r) & 3) ||
       (reinterpret_cast<uintptr_t>(dw) & 3) || (reinterpret_cast<uintptr_t>(dgamma) & 3) ||
       (reinterpret_cast<uintptr_t>(dbeta) & 3))
@@ -535,7 +551,8 @@ extern "C" int aeris_rmsnorm_adaln_bwd(const void* x, const float* w, const floa
   with_k(channels, [&](auto kc) {
     rc = launch_kernel(rmsnorm_adaln_bwd_kernel<decltype(kc)::value>, grid, dim3(kRowThreads),
                        smem, st, rw, static_cast<const bf16_t*>(x), w, gamma, r,
-                       static_cast<const bf16_t*>(dh), static_cast<bf16_t*>(dx), partial);
+                       static_cast<const bf16_t*>(dh), static_cast<const bf16_t*>(dres),
+                       static_cast<bf16_t*>(dx), partial);
   });
   if (rc != 0) return AERIS_ERR_HIP_LAUNCH;
   if (dw || dgamma || dbeta) {

@@ -211,6 +211,13 @@ def test_layer_ops_reject_bad_arguments_before_launching():
                                        None) == -8
     assert lib.aeris_rmsnorm_adaln_bwd(a, a, a, a, a, 8, 4, 64, a, None, None, None, None, need,
                                        None) == -1
+    # the residual form: same checks, dres optional but aligned
+    assert lib.aeris_rmsnorm_adaln_bwd_residual(a, a, a, a, a, None, 8, 4, 64, a, None, None, None, a,
+                                                need - 1, None) == -8
+    assert lib.aeris_rmsnorm_adaln_bwd_residual(a, a, a, a, a, odd, 8, 4, 64, a, None, None, None, a,
+                                                need, None) == -7
+    assert lib.aeris_rmsnorm_adaln_bwd_residual(a, a, a, a, None, a, 8, 4, 64, a, None, None, None, a,
+                                                need, None) == -1
     assert lib.aeris_gate_residual_fwd(a, None, a, 8, 4, 64, a, None) == -1
     assert lib.aeris_gate_residual_fwd(a, a, a, 8, 4, 64, odd, None) == -7
     assert lib.aeris_gate_residual_bwd_workspace_bytes(8, 4, 64) == 2 * 64 * 4

@@ -364,3 +364,31 @@ def test_linear_bwd_against_scalar_loops_autograd_and_differences():
         bo.linear_bwd(x, weight, dy.T)
     with pytest.raises(ValueError):
         bo.linear_bwd(x, weight.T, dy)
+
+
+def test_rmsnorm_bwd_residual_against_autograd_of_a_residual_layer():
+    """out = x + c * h(x) (a branch that scales the normalised rows): the gradient of
+    <out, dout> with respect to x is dout + the normalisation's backward of c * dout."""
+    rng = np.random.default_rng(91)
+    n, c, rows, eps = 6, 24, 3, 1e-5
+    x, dout = _rand(rng, n, c), _rand(rng, n, c)
+    w = 1.0 + 0.1 * _rand(rng, c)
+    gamma, beta = 0.3 * _rand(rng, 2, c), _rand(rng, 2, c)
+    scale = 0.7
+    dx, dw, dgamma, dbeta = bo.rmsnorm_adaln_bwd_residual(x, w, gamma, beta, eps, rows, scale * dout, dout)
+    tx = torch.tensor(x, requires_grad=True)
+    tw = torch.tensor(w, requires_grad=True)
+    tg = torch.tensor(gamma, requires_grad=True)
+    tb = torch.tensor(beta, requires_grad=True)
+    b = torch.arange(n) // rows
+    th = tx * torch.rsqrt((tx * tx).mean(dim=1, keepdim=True) + eps) * tw * (1 + tg[b]) + tb[b]
+    ((tx + scale * th) * torch.tensor(dout)).sum().backward()
+    np.testing.assert_allclose(dx, tx.grad.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dw, tw.grad.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dgamma, tg.grad.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dbeta, tb.grad.numpy(), rtol=0, atol=1e-12)
+    # no residual gradient: the plain backward
+    plain = bo.rmsnorm_adaln_bwd(x, w, gamma, beta, eps, rows, dout)
+    again = bo.rmsnorm_adaln_bwd_residual(x, w, gamma, beta, eps, rows, dout, np.zeros_like(x))
+    for a_, b_ in zip(plain, again):
+        np.testing.assert_array_equal(a_, b_)

@@ -127,8 +127,7 @@ def test_attention_half_of_a_layer_forward_and_backward():
                                     ws.data_ptr(), ws.numel(), stream)
     assert rc == 0
     tdh, tdwqkv = B.aeris_linear_bwd(th, twqkv, tdqkv)
-    tdxn, tdw, tdgamma, tdbeta = B.aeris_rmsnorm_adaln_bwd(tx, tw, tgamma, tr, tdh, rps)
-    tdx = (tdout.float() + tdxn.float())
+    tdx, tdw, tdgamma, tdbeta = B.aeris_rmsnorm_adaln_bwd(tx, tw, tgamma, tr, tdh, rps, dres=tdout)
     torch.cuda.synchronize()
 
     # ------------------------------------------------------------------ comparison
@@ -196,8 +195,7 @@ def test_swiglu_half_of_a_layer_forward_and_backward():
     tdg, tdwdown = B.aeris_linear_bwd(tg, twdown, tdy)
     tduv = B.aeris_swiglu_bwd(tuv, tdg)
     tdh, tdwup = B.aeris_linear_bwd(th, twup, tduv)
-    tdxn, tdw, tdgamma, tdbeta = B.aeris_rmsnorm_adaln_bwd(tx, tw, tgamma, tr, tdh, rps)
-    tdx = tdout.float() + tdxn.float()
+    tdx, tdw, tdgamma, tdbeta = B.aeris_rmsnorm_adaln_bwd(tx, tw, tgamma, tr, tdh, rps, dres=tdout)
     torch.cuda.synchronize()
 
     # every hand-over is one bf16 rounding on both sides; a value next to a rounding boundary may

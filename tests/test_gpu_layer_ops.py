@@ -114,6 +114,15 @@ def test_rmsnorm_adaln_forward_and_backward(nb, rps, C):
     sum_close("dgamma", tdgamma, dgamma)
     sum_close("dbeta", tdbeta, dbeta)
 
+    # with the residual connection closed in the same pass: dx + dres, rounded once; the
+    # parameter gradients do not change by a bit
+    rb_, r64 = activations(300 + C, n, C, spread=0.5)
+    tdx2, tdw2, tdgamma2, tdbeta2 = B.aeris_rmsnorm_adaln_bwd(tx, tw, tgamma, tr, tdh, rps, dres=to_dev(rb_))
+    torch.cuda.synchronize()
+    dx2, _, _, _ = bo.rmsnorm_adaln_bwd_residual(x64, w64, gamma64, beta64, eps, rps, g64, r64)
+    bf16_close("dx+dres", tdx2, dx2, 2.0 ** -20 * (term + np.abs(r64)) + r[:, None] * np.abs(nrm) * mean_err)
+    assert torch.equal(tdw, tdw2) and torch.equal(tdgamma, tdgamma2) and torch.equal(tdbeta, tdbeta2)
+
 
 def test_rmsnorm_adaln_without_r_and_without_parameter_gradients():
     nb, rps, C = 2, 50, 256
