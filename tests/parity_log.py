@@ -1,13 +1,14 @@
 """Record of measured parity errors (test infrastructure).
 
 Every GPU-vs-oracle comparison appends one row here; at the end of the session the rows are
-written as a table to gpurun_out/parity_errors.txt (and printed with `pytest -s`), so that the
-measured errors, not only pass/fail, are on record.
+written as a table to parity_errors.txt in the run's output folder (OUT_DIR below; also printed
+with `pytest -s`), so that the measured errors, not only pass/fail, are on record.
 """
 import os
 
 ROWS = []
 current_test = ""
+OUT_DIR = "gpurun_out"      # relative to the repository root
 
 HEADER = "%-78s %-5s %-4s %10s %10s %10s %10s %10s" % (
     "test", "what", "out", "rel_l2", "max_abs", "max|ref|", "abs_tol", "|bnd|/|ref|")
@@ -25,7 +26,7 @@ def write():
     if not ROWS:
         return
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    out_dir = os.path.join(root, "gpurun_out")
+    out_dir = os.path.join(root, OUT_DIR)
     try:
         os.makedirs(out_dir, exist_ok=True)
         with open(os.path.join(out_dir, "parity_errors.txt"), "w") as f:
